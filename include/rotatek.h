@@ -1,0 +1,183 @@
+/*
+ * rotatek.h -- C ABI of the RotateK hot path on AMD MI355X (gfx950).
+ *
+ * RotateK (arXiv 2605.19218) prunes Key-cache channels head-wise after an
+ * orthogonal PCA rotation R of the channel space.  This library implements
+ * the prefill-side construction of the rotated, pruned cache (Alg. 1 with the
+ * full eigendecomposition of Sec. 3.2 as the solver) and the decode-step
+ * attention over it (Alg. 2 steps 1-3 and 6, realised as the split-K /
+ * merge pair of App. C).
+ *
+ * Conventions
+ *   - Every tensor argument is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or retains tensor memory; scratch comes
+ *     from a caller-provided workspace sized by rk_*_workspace_size().
+ *   - All kernels are enqueued on the caller's stream (`stream` is a
+ *     hipStream_t passed as void*; NULL = the default stream).  Calls are
+ *     asynchronous.  Argument validation is synchronous and precedes any launch.
+ *   - Every function returns rk_status; no C++ exception crosses the boundary.
+ *   - head_dim d must be 128.  `keep` (the paper's k, App. C's d_keep) is
+ *     1..128.  dtype is the storage type of K, V, q, out and of the packed
+ *     cache; R, R_r, mu, delta_mu, eigenvalues and all scratch are fp32.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads) (App. C: R is
+ *     indexed [B, H_kv, d, d_keep]).
+ *   - Cache layout: packed rotated keys K~ [B, H_kv, capacity, keep] and
+ *     values V [B, H_kv, capacity, d], both contiguous, rows = tokens.
+ *   - Sequence lengths live on the device (int32 seq_len[B]); the host gives
+ *     an upper bound max_seq_len that sizes the grids.  Kernels never read or
+ *     write rows >= min(seq_len[b], capacity).
+ */
+#ifndef ROTATEK_H
+#define ROTATEK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RK_OK = 0,
+    RK_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, H_q % H_kv != 0, ... */
+    RK_ERR_UNSUPPORTED = 2,   /* head_dim != 128, unknown dtype                        */
+    RK_ERR_CAPACITY = 3,      /* more rows than `capacity`                             */
+    RK_ERR_WORKSPACE = 4,     /* workspace NULL or smaller than rk_*_workspace_size()  */
+    RK_ERR_HIP = 5,           /* a HIP call failed; text in rk_last_error()            */
+    RK_ERR_NO_DEVICE = 6      /* arguments are valid but the context has no device     */
+} rk_status;
+
+enum { RK_F32 = 0, RK_BF16 = 1 };
+
+/* rk_fit_rotation flags */
+enum {
+    RK_FIT_CENTER = 1u        /* subtract the per-head channel mean (Alg. 1 steps 1-2).
+                                 Without it the scatter is the literal K^T K.          */
+};
+
+/* rk_set_option keys */
+enum {
+    RK_OPT_FORCE_GENERIC = 1, /* value != 0: use the plain (non-MFMA) kernels everywhere  */
+    RK_OPT_DECODE_SPLITS = 2  /* value > 0: fix the split-K factor N_s; 0 = automatic     */
+};
+
+#define RK_DEVICE_NONE (-1)
+
+typedef struct rk_ctx rk_ctx;
+
+/* Shape of one attention layer's cache; shared by all calls. */
+typedef struct {
+    int32_t batch;            /* B                                                    */
+    int32_t n_q_heads;        /* H_q                                                  */
+    int32_t n_kv_heads;       /* H_kv, divides H_q                                    */
+    int32_t head_dim;         /* d = 128                                              */
+    int32_t keep;             /* r: kept channels per head, 1..d                      */
+    int32_t dtype;            /* RK_F32 | RK_BF16                                     */
+    int32_t capacity;         /* rows allocated per (b, h_kv) in K~ and V             */
+    int32_t max_seq_len;      /* host upper bound on seq_len[b]                       */
+    const int32_t* seq_len;   /* device [B]: tokens currently cached per sequence     */
+} rk_layout;
+
+/* Where the unrotated prefill Keys (or Values) come from.
+ * Row t of head (b, h) is at data + b*stride_b + h*stride_h + row*stride_t
+ * (strides in ELEMENTS, channels contiguous), where
+ *   row = t                                if tok_idx == NULL, t < n_b
+ *   row = tok_idx[tok_off[b] + t]          otherwise,          t < n_b
+ * and n_b = tok_off[b+1]-tok_off[b] (token list), else n_tokens_dev[b]
+ * (if given), else n_tokens.  n_tokens is always a host upper bound on n_b.
+ * The token list is the stand-in for a token pruner's keep set (Fig. 3a).    */
+typedef struct {
+    const void* data;
+    int64_t stride_b, stride_h, stride_t;
+    int32_t n_tokens;
+    const int32_t* n_tokens_dev;   /* device [B] or NULL  */
+    const int32_t* tok_idx;        /* device or NULL      */
+    const int64_t* tok_off;        /* device [B+1]; required with tok_idx */
+} rk_rows;
+
+/* Outputs of rk_fit_rotation (all device, fp32 unless noted). */
+typedef struct {
+    float* R;            /* [B,H_kv,d,d]  column c = eigenvector of eigvals[c] (solver order) */
+    float* eigvals;      /* [B,H_kv,d]    eigenvalues of C_q, same column order                */
+    uint8_t* mask;       /* [B,H_kv,d]    1 = column kept (its eigenvalue ranks among the top r) */
+    int32_t* keep_idx;   /* [B,H_kv,r]    keep_idx[j] = column whose eigenvalue has rank j      */
+    float* R_r;          /* [B,H_kv,d,r]  R_r[:, j] = R[:, keep_idx[j]]  (the paper's R_k)      */
+    float* mu;           /* [B,H_kv,d]    per-head channel mean of the fitted Keys             */
+    float* delta_mu;     /* [B,H_kv,d]    mu - R_r R_r^T mu  (Alg. 1 step 15)                   */
+    float* cov;          /* optional [B,H_kv,d,d]: the un-weighted scatter of Alg. 1 step 3     */
+} rk_fit_out;
+
+/* ---- context ------------------------------------------------------------- */
+/* Create a context bound to HIP device `device`.  RK_DEVICE_NONE makes a
+ * host-only context: every entry point then validates its arguments exactly
+ * as usual and returns RK_ERR_NO_DEVICE in place of launching.               */
+rk_status rk_create(rk_ctx** out, int device);
+rk_status rk_destroy(rk_ctx* ctx);
+const char* rk_status_str(rk_status s);
+const char* rk_last_error(const rk_ctx* ctx);          /* text of the last failure */
+rk_status rk_set_option(rk_ctx* ctx, int32_t key, int64_t value);
+
+/* Validate a layout on the host (also done inside every entry point). */
+rk_status rk_validate_layout(const rk_layout* L);
+
+/* Bytes of workspace rk_fit_rotation needs for at most max_tokens rows per sequence. */
+size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens);
+/* Bytes of workspace rk_decode_attn needs (depends on batch, heads, max_seq_len). */
+size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L);
+/* The split-K plan rk_decode_attn will use: N_s and tokens per split
+ * (App. C: N_s = max(1, min(ceil(S_v / BLOCK_N), 64)) on the A100; here it is
+ * sized to fill 256 compute units).                                          */
+rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split);
+
+/* ---- Alg. 1 steps 1-13 with the full eigendecomposition + keep-mask ---------
+ * Per (b, h_kv): mu and the centered scatter C = (K-mu)^T (K-mu) of the rows
+ * described by `keys` (Alg. 1 steps 1-3); C_q = (sigma sigma^T) .* C (step 5,
+ * Eq. 4; sigma [B,H_kv,d] fp32 device or NULL = ones); all d eigenpairs of
+ * C_q ("Query-Weighted PCA": R = eigenvectors of C_q); rank of every
+ * eigenvalue (descending, ties -> lower column) -> mask, keep_idx, R_r;
+ * delta_mu (step 15).  n_b = 0 gives mu = 0, C = 0 (R = I).
+ * Errors: INVALID_ARG (NULL required pointer, bad strides/sizes), UNSUPPORTED,
+ * WORKSPACE, HIP.                                                             */
+rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys,
+                          const float* sigma, uint32_t flags, const rk_fit_out* out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* R_r[:, j] = R[:, keep_idx[j]] for every (b, h_kv): re-derives the d x r form
+ * the kernels read from the canonical (R, keep_idx) state.                    */
+rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R,
+                             const int32_t* keep_idx, float* R_r, void* stream);
+
+/* ---- Alg. 1 step 14: K~ = K R_k, rounded once to the cache dtype ------------
+ * Writes rows [0, n_b) of k_packed[b, h] (n_b as defined at rk_rows; must be
+ * <= capacity, checked on the host against keys->n_tokens).  If `values` is
+ * non-NULL its rows are copied (gathered through the same token list) into
+ * v_cache.  If seq_len_out is non-NULL it receives n_b per sequence.
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY, HIP.                            */
+rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* R_r,
+                      void* k_packed, const rk_rows* values, void* v_cache,
+                      int32_t* seq_len_out, void* stream);
+
+/* ---- frozen-R append of one token per sequence ------------------------------
+ * k~ = k_new R_r (R is fitted once at the end of prefill and reused, Sec. 3.2
+ * Step (1)); writes row seq_len[b] of k_packed and v_cache for every KV head,
+ * then seq_len[b] += 1 on the device.  k_new, v_new: [B,H_kv,d] in L->dtype.
+ * Returns RK_ERR_CAPACITY if L->max_seq_len + 1 > capacity (nothing is
+ * launched); on the device a sequence already at capacity is left untouched.  */
+rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new,
+                    const float* R_r, void* k_packed, void* v_cache, int32_t* seq_len, void* stream);
+
+/* ---- Alg. 2 steps 1-3, 6 over the packed cache (App. C phases 1 and 2) ------
+ * q~ = q R_r, b = q . delta_mu (delta_mu NULL = no bias), scores
+ * (q~ . K~_n + b) * scale with scale = 1/sqrt(d) when `scale` <= 0, softmax over
+ * the seq_len[b] cached tokens, out = P V.  q, out: [B,H_q,d] in L->dtype.
+ * A sequence with seq_len[b] = 0 yields zeros.
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (max_seq_len > capacity),
+ * WORKSPACE, HIP.                                                             */
+rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                         const void* v_cache, const float* R_r, const float* delta_mu, float scale,
+                         void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROTATEK_H */

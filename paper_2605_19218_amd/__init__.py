@@ -1,0 +1,235 @@
+"""RotateK hot path for AMD MI355X: thin ctypes binding of librotatek.so.
+
+The functions here have the names and argument order of the C ABI declared in
+include/rotatek.h and only marshal arguments (device pointers, strides, sizes);
+every step of the path runs in the HIP kernels.  PyTorch is used by callers for
+device memory and streams only.  There is no CPU fallback: importing works
+without a GPU (so that argument validation can be exercised through a host-only
+context), but a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Any, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librotatek.so")
+
+RK_OK, RK_ERR_INVALID_ARG, RK_ERR_UNSUPPORTED, RK_ERR_CAPACITY, RK_ERR_WORKSPACE, RK_ERR_HIP, RK_ERR_NO_DEVICE = range(7)
+RK_F32, RK_BF16 = 0, 1
+RK_FIT_CENTER = 1
+RK_OPT_FORCE_GENERIC, RK_OPT_DECODE_SPLITS = 1, 2
+RK_DEVICE_NONE = -1
+
+EXPORTS = [
+    "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
+    "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
+    "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn",
+]
+
+
+class rk_layout(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("keep", C.c_int32), ("dtype", C.c_int32),
+                ("capacity", C.c_int32), ("max_seq_len", C.c_int32), ("seq_len", C.c_void_p)]
+
+
+class rk_rows(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64),
+                ("stride_t", C.c_int64), ("n_tokens", C.c_int32), ("n_tokens_dev", C.c_void_p),
+                ("tok_idx", C.c_void_p), ("tok_off", C.c_void_p)]
+
+
+class rk_fit_out(C.Structure):
+    _fields_ = [("R", C.c_void_p), ("eigvals", C.c_void_p), ("mask", C.c_void_p), ("keep_idx", C.c_void_p),
+                ("R_r", C.c_void_p), ("mu", C.c_void_p), ("delta_mu", C.c_void_p), ("cov", C.c_void_p)]
+
+
+class RotateKError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"rotatek status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load librotatek.so (built by paper_2605_19218_amd/build.py); loud failure if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u32, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float, C.c_size_t
+        PL, PR, PF = C.POINTER(rk_layout), C.POINTER(rk_rows), C.POINTER(rk_fit_out)
+        L.rk_create.argtypes = [C.POINTER(vp), C.c_int]
+        L.rk_destroy.argtypes = [vp]
+        L.rk_status_str.argtypes = [C.c_int]
+        L.rk_status_str.restype = C.c_char_p
+        L.rk_last_error.argtypes = [vp]
+        L.rk_last_error.restype = C.c_char_p
+        L.rk_set_option.argtypes = [vp, i32, i64]
+        L.rk_validate_layout.argtypes = [PL]
+        L.rk_fit_workspace_size.argtypes = [PL, i32]
+        L.rk_fit_workspace_size.restype = sz
+        L.rk_decode_workspace_size.argtypes = [vp, PL]
+        L.rk_decode_workspace_size.restype = sz
+        L.rk_decode_plan.argtypes = [vp, PL, C.POINTER(i32), C.POINTER(i32)]
+        L.rk_fit_rotation.argtypes = [vp, PL, PR, vp, u32, PF, vp, sz, vp]
+        L.rk_gather_rotation.argtypes = [vp, PL, vp, vp, vp, vp]
+        L.rk_compress.argtypes = [vp, PL, PR, vp, vp, PR, vp, vp, vp]
+        L.rk_append.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp]
+        L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+        for name in EXPORTS:
+            if name not in ("rk_status_str", "rk_last_error", "rk_fit_workspace_size", "rk_decode_workspace_size"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x: Any) -> Optional[int]:
+    """Device pointer of a tensor-like (anything with data_ptr()), an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _nbytes(x: Any) -> int:
+    return int(x.numel() * x.element_size())
+
+
+def _stream(stream: Any) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)        # torch.cuda.Stream
+
+
+def _check(ctx, status: int):
+    if status != RK_OK:
+        text = lib().rk_last_error(ctx).decode() if ctx else ""
+        raise RotateKError(status, text or lib().rk_status_str(status).decode())
+
+
+# ---- argument holders ------------------------------------------------------
+@dataclass
+class Layout:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    keep: int
+    dtype: int
+    capacity: int
+    max_seq_len: int
+    seq_len: Any = None           # device int32 [batch]
+    head_dim: int = 128
+
+    def c(self) -> rk_layout:
+        return rk_layout(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.keep, self.dtype,
+                         self.capacity, self.max_seq_len, _ptr(self.seq_len))
+
+
+@dataclass
+class Rows:
+    """Rows of a [B, H_kv, N, d] tensor-like (any strides, channels contiguous)."""
+    data: Any
+    n_tokens: int
+    n_tokens_dev: Any = None
+    tok_idx: Any = None
+    tok_off: Any = None
+    strides: Optional[tuple] = None      # (stride_b, stride_h, stride_t) in elements
+
+    def c(self) -> rk_rows:
+        st = self.strides if self.strides is not None else tuple(self.data.stride()[:3])
+        return rk_rows(_ptr(self.data), st[0], st[1], st[2], self.n_tokens, _ptr(self.n_tokens_dev),
+                       _ptr(self.tok_idx), _ptr(self.tok_off))
+
+
+@dataclass
+class FitOut:
+    R: Any
+    eigvals: Any
+    mask: Any
+    keep_idx: Any
+    R_r: Any
+    mu: Any
+    delta_mu: Any
+    cov: Any = None
+
+    def c(self) -> rk_fit_out:
+        return rk_fit_out(*[_ptr(getattr(self, f)) for f in
+                            ("R", "eigvals", "mask", "keep_idx", "R_r", "mu", "delta_mu", "cov")])
+
+
+# ---- the ABI, same names -----------------------------------------------------
+def rk_create(device: int = 0) -> int:
+    h = C.c_void_p()
+    st = lib().rk_create(C.byref(h), int(device))
+    if st != RK_OK:
+        raise RotateKError(st, lib().rk_status_str(st).decode())
+    return h.value
+
+
+def rk_destroy(ctx) -> None:
+    lib().rk_destroy(ctx)
+
+
+def rk_set_option(ctx, key: int, value: int) -> None:
+    _check(ctx, lib().rk_set_option(ctx, key, value))
+
+
+def rk_validate_layout(layout: Layout) -> int:
+    return lib().rk_validate_layout(C.byref(layout.c()))
+
+
+def rk_fit_workspace_size(layout: Layout, max_tokens: int) -> int:
+    return int(lib().rk_fit_workspace_size(C.byref(layout.c()), int(max_tokens)))
+
+
+def rk_decode_workspace_size(ctx, layout: Layout) -> int:
+    return int(lib().rk_decode_workspace_size(ctx, C.byref(layout.c())))
+
+
+def rk_decode_plan(ctx, layout: Layout):
+    s, t = C.c_int32(), C.c_int32()
+    _check(ctx, lib().rk_decode_plan(ctx, C.byref(layout.c()), C.byref(s), C.byref(t)))
+    return s.value, t.value
+
+
+def rk_fit_rotation(ctx, layout: Layout, keys: Rows, sigma, flags: int, out: FitOut, workspace, stream=None,
+                    workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    _check(ctx, lib().rk_fit_rotation(ctx, C.byref(layout.c()), C.byref(keys.c()), _ptr(sigma), flags,
+                                      C.byref(out.c()), _ptr(workspace), wb, _stream(stream)))
+
+
+def rk_gather_rotation(ctx, layout: Layout, R, keep_idx, R_r, stream=None) -> None:
+    _check(ctx, lib().rk_gather_rotation(ctx, C.byref(layout.c()), _ptr(R), _ptr(keep_idx), _ptr(R_r),
+                                         _stream(stream)))
+
+
+def rk_compress(ctx, layout: Layout, keys: Rows, R_r, k_packed, values: Optional[Rows] = None, v_cache=None,
+                seq_len_out=None, stream=None) -> None:
+    vrows = C.byref(values.c()) if values is not None else None
+    _check(ctx, lib().rk_compress(ctx, C.byref(layout.c()), C.byref(keys.c()), _ptr(R_r), _ptr(k_packed), vrows,
+                                  _ptr(v_cache), _ptr(seq_len_out), _stream(stream)))
+
+
+def rk_append(ctx, layout: Layout, k_new, v_new, R_r, k_packed, v_cache, seq_len, stream=None) -> None:
+    _check(ctx, lib().rk_append(ctx, C.byref(layout.c()), _ptr(k_new), _ptr(v_new), _ptr(R_r), _ptr(k_packed),
+                                _ptr(v_cache), _ptr(seq_len), _stream(stream)))
+
+
+def rk_decode_attn(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, scale: float, out, workspace,
+                   stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    _check(ctx, lib().rk_decode_attn(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache), _ptr(R_r),
+                                     _ptr(delta_mu), float(scale), _ptr(out), _ptr(workspace), wb,
+                                     _stream(stream)))

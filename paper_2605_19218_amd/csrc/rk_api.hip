@@ -1,0 +1,348 @@
+// C ABI of the RotateK hot path: argument validation, workspace carving and
+// kernel launches.  See include/rotatek.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "rk_kernels.hpp"
+#include "rotatek.h"
+
+struct rk_ctx {
+    int device;           // RK_DEVICE_NONE: host-only validation context
+    int n_cu;
+    int force_generic;
+    int decode_splits;
+    char err[256];
+};
+
+namespace {
+
+using namespace rk;
+
+rk_status fail(rk_ctx* ctx, rk_status s, const char* fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+rk_status hip_fail(rk_ctx* ctx, hipError_t e, const char* what)
+{
+    return fail(ctx, RK_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t elem_size(int dtype) { return dtype == RK_F32 ? 4 : 2; }
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+rk_status check_layout(rk_ctx* ctx, const rk_layout* L)
+{
+    if (!L) return fail(ctx, RK_ERR_INVALID_ARG, "layout is NULL");
+    if (L->head_dim != D) return fail(ctx, RK_ERR_UNSUPPORTED, "head_dim %d: only 128 is supported", L->head_dim);
+    if (L->dtype != RK_F32 && L->dtype != RK_BF16) return fail(ctx, RK_ERR_UNSUPPORTED, "unknown dtype %d", L->dtype);
+    if (L->batch < 1 || L->n_q_heads < 1 || L->n_kv_heads < 1)
+        return fail(ctx, RK_ERR_INVALID_ARG, "batch/head counts must be positive");
+    if (L->batch > 65535 || L->n_q_heads > 65535) return fail(ctx, RK_ERR_INVALID_ARG, "batch/head counts exceed 65535");
+    if (L->n_q_heads % L->n_kv_heads != 0)
+        return fail(ctx, RK_ERR_INVALID_ARG, "n_q_heads %d is not a multiple of n_kv_heads %d", L->n_q_heads, L->n_kv_heads);
+    if (L->keep < 1 || L->keep > D) return fail(ctx, RK_ERR_INVALID_ARG, "keep %d outside 1..128", L->keep);
+    if (L->capacity < 1) return fail(ctx, RK_ERR_INVALID_ARG, "capacity must be positive");
+    if (L->max_seq_len < 0) return fail(ctx, RK_ERR_INVALID_ARG, "max_seq_len is negative");
+    return RK_OK;
+}
+
+rk_status check_rows(rk_ctx* ctx, const rk_layout* L, const rk_rows* r, const char* name)
+{
+    if (!r || !r->data) return fail(ctx, RK_ERR_INVALID_ARG, "%s: NULL", name);
+    if (r->n_tokens < 0) return fail(ctx, RK_ERR_INVALID_ARG, "%s: n_tokens is negative", name);
+    if (r->tok_idx && !r->tok_off) return fail(ctx, RK_ERR_INVALID_ARG, "%s: tok_idx given without tok_off", name);
+    if (r->stride_t < D || r->stride_b < 0 || r->stride_h < 0)
+        return fail(ctx, RK_ERR_INVALID_ARG, "%s: bad strides", name);
+    const int64_t ea = 16 / (int64_t)elem_size(L->dtype);    // elements per 16 bytes
+    if (((uintptr_t)r->data & 15) || r->stride_t % ea || r->stride_b % ea || r->stride_h % ea)
+        return fail(ctx, RK_ERR_INVALID_ARG, "%s: rows must be 16-byte aligned", name);
+    return RK_OK;
+}
+
+RowsDev to_dev(const rk_rows* r)
+{
+    RowsDev d;
+    d.data = r->data; d.sb = r->stride_b; d.sh = r->stride_h; d.st = r->stride_t;
+    d.n_tokens = r->n_tokens; d.n_dev = r->n_tokens_dev; d.tok_idx = r->tok_idx; d.tok_off = r->tok_off;
+    return d;
+}
+
+int cov_chunks(int max_tokens) { int n = (max_tokens + COV_CHUNK - 1) / COV_CHUNK; return n < 1 ? 1 : n; }
+
+struct FitWs { size_t part_S, part_sum, cov, total; };
+FitWs fit_ws(const rk_layout* L, int max_tokens)
+{
+    size_t U = (size_t)L->batch * L->n_kv_heads, nc = (size_t)cov_chunks(max_tokens);
+    FitWs w;
+    w.part_S = 0;
+    w.part_sum = align_up(w.part_S + U * nc * D * D * sizeof(float), 256);
+    w.cov = align_up(w.part_sum + U * nc * D * sizeof(float), 256);
+    w.total = align_up(w.cov + U * D * D * sizeof(float), 256);
+    return w;
+}
+
+bool use_mfma_decode(const rk_ctx* ctx, const rk_layout* L)
+{
+    return !(ctx && ctx->force_generic) && decode_mfma_supported(L->dtype, L->keep);
+}
+
+void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tps_out)
+{
+    const int G = L->n_q_heads / L->n_kv_heads;
+    const bool mfma = use_mfma_decode(ctx, L);
+    const long units = mfma ? (long)L->batch * L->n_kv_heads * ((G + 15) / 16) : (long)L->batch * L->n_q_heads;
+    const int maxL = L->max_seq_len > 0 ? L->max_seq_len : 1;
+    const int tiles = (maxL + 127) / 128;
+    const int n_cu = ctx ? ctx->n_cu : 256;
+    int S;
+    if (ctx && ctx->decode_splits > 0) S = ctx->decode_splits;
+    else {
+        long target = 4L * n_cu;
+        S = (int)((target + units - 1) / units);
+        if (S > 64) S = 64;
+    }
+    if (S > tiles) S = tiles;
+    if (S < 1) S = 1;
+    const int tiles_per = (tiles + S - 1) / S;
+    const int tps = tiles_per * 128;
+    *S_out = (maxL + tps - 1) / tps;
+    *tps_out = tps;
+}
+
+hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+}  // namespace
+
+extern "C" {
+
+const char* rk_status_str(rk_status s)
+{
+    switch (s) {
+        case RK_OK: return "ok";
+        case RK_ERR_INVALID_ARG: return "invalid argument";
+        case RK_ERR_UNSUPPORTED: return "unsupported configuration";
+        case RK_ERR_CAPACITY: return "cache capacity exceeded";
+        case RK_ERR_WORKSPACE: return "workspace missing or too small";
+        case RK_ERR_HIP: return "HIP error";
+        case RK_ERR_NO_DEVICE: return "context has no device";
+    }
+    return "unknown status";
+}
+
+rk_status rk_create(rk_ctx** out, int device)
+{
+    if (!out) return RK_ERR_INVALID_ARG;
+    *out = nullptr;
+    rk_ctx* c = new (std::nothrow) rk_ctx();
+    if (!c) return RK_ERR_INVALID_ARG;
+    memset(c, 0, sizeof(*c));
+    c->device = device;
+    c->n_cu = 256;
+    if (device != RK_DEVICE_NONE) {
+        if (device < 0) { delete c; return RK_ERR_INVALID_ARG; }
+        hipDeviceProp_t prop;
+        hipError_t e = hipGetDeviceProperties(&prop, device);
+        if (e != hipSuccess) { delete c; return RK_ERR_HIP; }
+        c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    *out = c;
+    return RK_OK;
+}
+
+rk_status rk_destroy(rk_ctx* ctx)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    delete ctx;
+    return RK_OK;
+}
+
+const char* rk_last_error(const rk_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+rk_status rk_set_option(rk_ctx* ctx, int32_t key, int64_t value)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    switch (key) {
+        case RK_OPT_FORCE_GENERIC: ctx->force_generic = value != 0; return RK_OK;
+        case RK_OPT_DECODE_SPLITS:
+            if (value < 0 || value > 4096) return fail(ctx, RK_ERR_INVALID_ARG, "decode splits %lld outside 0..4096", (long long)value);
+            ctx->decode_splits = (int)value;
+            return RK_OK;
+        default: return fail(ctx, RK_ERR_INVALID_ARG, "unknown option %d", key);
+    }
+}
+
+rk_status rk_validate_layout(const rk_layout* L) { return check_layout(nullptr, L); }
+
+size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens)
+{
+    if (check_layout(nullptr, L) != RK_OK || max_tokens < 0) return 0;
+    return fit_ws(L, max_tokens).total;
+}
+
+size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L)
+{
+    if (check_layout(nullptr, L) != RK_OK) return 0;
+    int S, tps;
+    decode_plan(ctx, L, &S, &tps);
+    return align_up((size_t)L->batch * L->n_q_heads * S * (D + 2) * sizeof(float), 256);
+}
+
+rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split)
+{
+    rk_status s = check_layout(nullptr, L);
+    if (s != RK_OK) return s;
+    if (!n_splits || !tokens_per_split) return RK_ERR_INVALID_ARG;
+    int S, tps;
+    decode_plan(ctx, L, &S, &tps);
+    *n_splits = S;
+    *tokens_per_split = tps;
+    return RK_OK;
+}
+
+rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* sigma,
+                          uint32_t flags, const rk_fit_out* out, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    s = check_rows(ctx, L, keys, "keys");
+    if (s != RK_OK) return s;
+    if (!out || !out->R || !out->eigvals || !out->mask || !out->keep_idx || !out->R_r || !out->mu || !out->delta_mu)
+        return fail(ctx, RK_ERR_INVALID_ARG, "fit outputs: a required pointer is NULL");
+    if (flags & ~(uint32_t)RK_FIT_CENTER) return fail(ctx, RK_ERR_INVALID_ARG, "unknown fit flags 0x%x", flags);
+    const FitWs w = fit_ws(L, keys->n_tokens);
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))
+        return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const int B = L->batch, Hkv = L->n_kv_heads, U = B * Hkv;
+    const int nc = cov_chunks(keys->n_tokens);
+    char* ws = (char*)workspace;
+    float* part_S = (float*)(ws + w.part_S);
+    float* part_sum = (float*)(ws + w.part_sum);
+    float* cov = out->cov ? out->cov : (float*)(ws + w.cov);
+    const RowsDev rows = to_dev(keys);
+    hipStream_t st = as_stream(stream);
+    e = launch_cov_partial(L->dtype, !ctx->force_generic, rows, B, Hkv, nc, part_S, part_sum, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "covariance launch");
+    e = launch_cov_finalize(rows, B, Hkv, nc, (flags & RK_FIT_CENTER) != 0, part_S, part_sum, cov, out->mu, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "covariance reduction launch");
+    e = launch_eig(U, cov, sigma, out->mu, L->keep, out->R, out->eigvals, out->mask, out->keep_idx, out->R_r,
+                   out->delta_mu, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "eigensolver launch");
+    return RK_OK;
+}
+
+rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R, const int32_t* keep_idx,
+                             float* R_r, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!R || !keep_idx || !R_r) return fail(ctx, RK_ERR_INVALID_ARG, "gather_rotation: NULL pointer");
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_gather_rotation(L->batch * L->n_kv_heads, L->keep, R, keep_idx, R_r, as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
+    return RK_OK;
+}
+
+rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* R_r, void* k_packed,
+                      const rk_rows* values, void* v_cache, int32_t* seq_len_out, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    s = check_rows(ctx, L, keys, "keys");
+    if (s != RK_OK) return s;
+    if (!R_r || !k_packed) return fail(ctx, RK_ERR_INVALID_ARG, "compress: R_r or k_packed is NULL");
+    if ((uintptr_t)k_packed & 15) return fail(ctx, RK_ERR_INVALID_ARG, "compress: k_packed must be 16-byte aligned");
+    if (values) {
+        s = check_rows(ctx, L, values, "values");
+        if (s != RK_OK) return s;
+        if (!v_cache || ((uintptr_t)v_cache & 15))
+            return fail(ctx, RK_ERR_INVALID_ARG, "compress: values given but v_cache is NULL or misaligned");
+        if (values->n_tokens != keys->n_tokens || values->tok_idx != keys->tok_idx ||
+            values->tok_off != keys->tok_off || values->n_tokens_dev != keys->n_tokens_dev)
+            return fail(ctx, RK_ERR_INVALID_ARG, "compress: values must use the same row selection as keys");
+    }
+    if (keys->n_tokens > L->capacity)
+        return fail(ctx, RK_ERR_CAPACITY, "compress: %d rows exceed capacity %d", keys->n_tokens, L->capacity);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    hipStream_t st = as_stream(stream);
+    e = launch_compress(L->dtype, !ctx->force_generic, to_dev(keys), L->batch, L->n_kv_heads, L->capacity, L->keep,
+                        R_r, k_packed, seq_len_out, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "compress launch");
+    if (values) {
+        e = launch_row_copy(L->dtype, to_dev(values), L->batch, L->n_kv_heads, L->capacity, v_cache, st);
+        if (e != hipSuccess) return hip_fail(ctx, e, "value copy launch");
+    }
+    return RK_OK;
+}
+
+rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new, const float* R_r,
+                    void* k_packed, void* v_cache, int32_t* seq_len, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!k_new || !v_new || !R_r || !k_packed || !v_cache || !seq_len)
+        return fail(ctx, RK_ERR_INVALID_ARG, "append: NULL pointer");
+    if (L->max_seq_len + 1 > L->capacity)
+        return fail(ctx, RK_ERR_CAPACITY, "append: %d + 1 rows exceed capacity %d", L->max_seq_len, L->capacity);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_append(L->dtype, L->batch, L->n_kv_heads, L->capacity, L->keep, k_new, v_new, R_r, k_packed,
+                      v_cache, seq_len, as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "append launch");
+    return RK_OK;
+}
+
+rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                         const void* v_cache, const float* R_r, const float* delta_mu, float scale, void* out,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!q || !k_packed || !v_cache || !R_r || !out || !L->seq_len)
+        return fail(ctx, RK_ERR_INVALID_ARG, "decode: NULL pointer (q, k_packed, v_cache, R_r, out, seq_len)");
+    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "decode: caches must be 16-byte aligned");
+    if (L->max_seq_len > L->capacity)
+        return fail(ctx, RK_ERR_CAPACITY, "decode: max_seq_len %d exceeds capacity %d", L->max_seq_len, L->capacity);
+    const size_t need = rk_decode_workspace_size(ctx, L);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
+        return fail(ctx, RK_ERR_WORKSPACE, "decode workspace: need %zu bytes, 16-byte aligned", need);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    int S, tps;
+    decode_plan(ctx, L, &S, &tps);
+    const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
+    e = launch_decode(L->dtype, use_mfma_decode(ctx, L), L->batch, L->n_q_heads, L->n_kv_heads, L->capacity,
+                      L->keep, S, tps, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, sc, out, (float*)workspace,
+                      as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
+    return RK_OK;
+}
+
+}  // extern "C"

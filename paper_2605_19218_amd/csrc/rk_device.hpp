@@ -1,0 +1,78 @@
+// Internal device-side helpers shared by the RotateK kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rk {
+
+constexpr int D = 128;                 // head dim the kernels are written for
+typedef uint16_t bf16_t;               // raw bfloat16 storage
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// round-to-nearest-even (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float ld_elem(const float* p) { return *p; }
+__device__ __forceinline__ float ld_elem(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void st_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// split an fp32 value into a bf16 head and a bf16 remainder: x ~= hi + lo to ~2^-17
+__device__ __forceinline__ void split_bf16(float x, __bf16& hi, __bf16& lo) {
+    hi = (__bf16)x;
+    lo = (__bf16)(x - (float)hi);
+}
+
+// Orders this wave's LDS writes before its later LDS reads by other lanes.  DS
+// operations of one wave execute in issue order, so only the compiler has to be
+// kept from moving them.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Device view of rk_rows (see rotatek.h).
+struct RowsDev {
+    const void* data;
+    int64_t sb, sh, st;
+    int32_t n_tokens;
+    const int32_t* n_dev;
+    const int32_t* tok_idx;
+    const int64_t* tok_off;
+};
+
+__device__ __forceinline__ int rows_count(const RowsDev& r, int b) {
+    int n;
+    if (r.tok_idx) n = (int)(r.tok_off[b + 1] - r.tok_off[b]);
+    else if (r.n_dev) n = r.n_dev[b];
+    else n = r.n_tokens;
+    n = n < 0 ? 0 : n;
+    return n < r.n_tokens ? n : r.n_tokens;
+}
+
+// element offset of logical row t of head (b, h)
+__device__ __forceinline__ int64_t rows_offset(const RowsDev& r, int b, int h, int t) {
+    int64_t row = r.tok_idx ? (int64_t)r.tok_idx[r.tok_off[b] + t] : (int64_t)t;
+    return (int64_t)b * r.sb + (int64_t)h * r.sh + row * r.st;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+}  // namespace rk

@@ -1,0 +1,36 @@
+// Host-side launch wrappers of the RotateK kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "rk_device.hpp"
+
+namespace rk {
+
+// ---- rk_fit.hip ------------------------------------------------------------
+// Tokens per covariance work-group; partials are [U, n_chunks, d*d] + [U, n_chunks, d].
+constexpr int COV_CHUNK = 512;
+hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int n_chunks,
+                              float* part_S, float* part_sum, hipStream_t st);
+hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center,
+                               const float* part_S, const float* part_sum, float* cov, float* mu,
+                               hipStream_t st);
+hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
+                      float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, hipStream_t st);
+hipError_t launch_gather_rotation(int U, int r, const float* R, const int32_t* keep_idx, float* Rr,
+                                  hipStream_t st);
+
+// ---- rk_compress.hip -------------------------------------------------------
+hipError_t launch_compress(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int cap, int r,
+                           const float* Rr, void* Kp, int32_t* seq_len_out, hipStream_t st);
+hipError_t launch_row_copy(int dtype, const RowsDev& rows, int B, int Hkv, int cap, void* dst, hipStream_t st);
+hipError_t launch_append(int dtype, int B, int Hkv, int cap, int r, const void* k_new, const void* v_new,
+                         const float* Rr, void* Kp, void* Vc, int32_t* seq_len, hipStream_t st);
+
+// ---- rk_decode.hip ---------------------------------------------------------
+// Partials: m [B,Hq,S], l [B,Hq,S], acc [B,Hq,S,d]; m is in the log2 domain.
+bool decode_mfma_supported(int dtype, int r);
+hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
+                         const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
+                         const int32_t* seq_len, float scale, void* out, float* ws, hipStream_t st);
+
+}  // namespace rk

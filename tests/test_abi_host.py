@@ -1,0 +1,146 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and validates arguments before touching a device."""
+import os
+import re
+
+import pytest
+
+import paper_2605_19218_amd as rk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PTR = 4096          # a fake, 16-byte aligned, non-NULL "device pointer"; never dereferenced
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = rk.rk_create(rk.RK_DEVICE_NONE)
+    yield c
+    rk.rk_destroy(c)
+
+
+def layout(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, keep=64, dtype=rk.RK_BF16, capacity=1024, max_seq_len=1000,
+                seq_len=PTR)
+    base.update(kw)
+    return rk.Layout(**base)
+
+
+def rows(n=1000, **kw):
+    base = dict(data=PTR, n_tokens=n, strides=(2 * 1024 * 128, 1024 * 128, 128))
+    base.update(kw)
+    return rk.Rows(**base)
+
+
+def fit_out(**kw):
+    base = dict(R=PTR, eigvals=PTR, mask=PTR, keep_idx=PTR, R_r=PTR, mu=PTR, delta_mu=PTR)
+    base.update(kw)
+    return rk.FitOut(**base)
+
+
+def status_of(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except rk.RotateKError as e:
+        return e.status
+    return rk.RK_OK
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "rotatek.h")).read()
+    declared = set(re.findall(r"\b(rk_[a-z_]+)\s*\(", text))
+    assert declared == set(rk.EXPORTS), declared ^ set(rk.EXPORTS)
+    L = rk.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_layout_validation():
+    assert rk.rk_validate_layout(layout()) == rk.RK_OK
+    assert rk.rk_validate_layout(layout(head_dim=64)) == rk.RK_ERR_UNSUPPORTED
+    assert rk.rk_validate_layout(layout(dtype=7)) == rk.RK_ERR_UNSUPPORTED
+    assert rk.rk_validate_layout(layout(n_q_heads=7)) == rk.RK_ERR_INVALID_ARG
+    assert rk.rk_validate_layout(layout(keep=0)) == rk.RK_ERR_INVALID_ARG
+    assert rk.rk_validate_layout(layout(keep=129)) == rk.RK_ERR_INVALID_ARG
+    assert rk.rk_validate_layout(layout(capacity=0)) == rk.RK_ERR_INVALID_ARG
+    assert rk.rk_validate_layout(layout(batch=0)) == rk.RK_ERR_INVALID_ARG
+    assert rk.lib().rk_validate_layout(None) == rk.RK_ERR_INVALID_ARG
+
+
+def test_no_device_context_validates_then_refuses(ctx):
+    lay = layout()
+    ws = rk.rk_decode_workspace_size(ctx, lay)
+    assert ws > 0
+    ok = (ctx, lay, PTR, PTR, PTR, PTR, PTR, 0.0, PTR, PTR)
+    assert status_of(rk.rk_decode_attn, *ok, workspace_bytes=ws) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_decode_attn, *ok, workspace_bytes=ws - 1) == rk.RK_ERR_WORKSPACE
+    assert status_of(rk.rk_decode_attn, ctx, lay, None, PTR, PTR, PTR, PTR, 0.0, PTR, PTR,
+                     workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_decode_attn, ctx, layout(seq_len=None), PTR, PTR, PTR, PTR, PTR, 0.0, PTR, PTR,
+                     workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_decode_attn, ctx, layout(max_seq_len=2000), PTR, PTR, PTR, PTR, PTR, 0.0, PTR, PTR,
+                     workspace_bytes=1 << 30) == rk.RK_ERR_CAPACITY
+    # delta_mu is optional
+    assert status_of(rk.rk_decode_attn, ctx, lay, PTR, PTR, PTR, PTR, None, 0.0, PTR, PTR,
+                     workspace_bytes=ws) == rk.RK_ERR_NO_DEVICE
+    assert "device" in rk.lib().rk_status_str(rk.RK_ERR_NO_DEVICE).decode()
+
+
+def test_fit_validation(ctx):
+    lay = layout()
+    ws = rk.rk_fit_workspace_size(lay, 1000)
+    assert ws > 0 and rk.rk_fit_workspace_size(lay, 2000) > ws
+    args = lambda **kw: (ctx, kw.get("lay", lay), kw.get("rows", rows()), None, kw.get("flags", rk.RK_FIT_CENTER),
+                         kw.get("out", fit_out()), PTR)
+    assert status_of(rk.rk_fit_rotation, *args(), workspace_bytes=ws) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_fit_rotation, *args(), workspace_bytes=ws - 1) == rk.RK_ERR_WORKSPACE
+    assert status_of(rk.rk_fit_rotation, *args(out=fit_out(R=None)), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(flags=8), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(rows=rows(data=None)), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(rows=rows(data=PTR + 2)), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(rows=rows(strides=(0, 0, 64))), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(rows=rows(tok_idx=PTR)), workspace_bytes=ws) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_fit_rotation, *args(rows=rows(tok_idx=PTR, tok_off=PTR)), workspace_bytes=ws) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_fit_rotation, *args(lay=layout(head_dim=96)), workspace_bytes=ws) == rk.RK_ERR_UNSUPPORTED
+    assert b"128" in rk.lib().rk_last_error(ctx)
+
+
+def test_compress_append_validation(ctx):
+    lay = layout()
+    assert status_of(rk.rk_compress, ctx, lay, rows(), PTR, PTR) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_compress, ctx, lay, rows(n=1025), PTR, PTR) == rk.RK_ERR_CAPACITY
+    assert status_of(rk.rk_compress, ctx, lay, rows(), None, PTR) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_compress, ctx, lay, rows(), PTR, PTR, values=rows(), v_cache=None) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_compress, ctx, lay, rows(), PTR, PTR, values=rows(n=999), v_cache=PTR) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_compress, ctx, lay, rows(), PTR, PTR, values=rows(), v_cache=PTR) == rk.RK_ERR_NO_DEVICE
+    ap = (PTR, PTR, PTR, PTR, PTR, PTR)
+    assert status_of(rk.rk_append, ctx, lay, *ap) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_append, ctx, layout(max_seq_len=1024), *ap) == rk.RK_ERR_CAPACITY
+    assert status_of(rk.rk_append, ctx, lay, PTR, None, PTR, PTR, PTR, PTR) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_gather_rotation, ctx, lay, PTR, PTR, PTR) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_gather_rotation, ctx, lay, PTR, None, PTR) == rk.RK_ERR_INVALID_ARG
+
+
+def test_decode_plan_and_options(ctx):
+    lay = layout(batch=8, n_q_heads=28, n_kv_heads=4, capacity=16384, max_seq_len=16384)
+    S, tps = rk.rk_decode_plan(ctx, lay)
+    assert S >= 1 and tps % 128 == 0 and S * tps >= 16384 and (S - 1) * tps < 16384
+    rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 5)
+    S5, tps5 = rk.rk_decode_plan(ctx, lay)
+    assert S5 <= 5 and S5 * tps5 >= 16384
+    rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 0)
+    assert rk.rk_decode_plan(ctx, lay) == (S, tps)
+    assert status_of(rk.rk_set_option, ctx, 99, 1) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_set_option, ctx, rk.RK_OPT_DECODE_SPLITS, -1) == rk.RK_ERR_INVALID_ARG
+    # a short cache never gets more splits than 128-token tiles
+    assert rk.rk_decode_plan(ctx, layout(max_seq_len=100))[0] == 1
+    assert rk.rk_decode_plan(ctx, layout(max_seq_len=0))[0] == 1
+
+
+def test_product_does_not_import_oracle():
+    """The product path must not route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2605_19218_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "rotatek_oracle" not in text, f

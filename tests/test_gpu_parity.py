@@ -1,0 +1,337 @@
+"""GPU-vs-oracle parity of the RotateK hot path, stage by stage and end to end,
+through the C ABI binding.  Tolerances (from the benchmark spec): mask and
+indices bit-exact; fp32 results max|x-y|/max|y| <= 1e-4; bf16 outputs
+max|x-y| <= 2e-2; packed bf16 Keys within one bf16 ulp plus the fp32
+accumulation bound derived below.
+
+Protocol for the eigenbasis (any orthonormal eigenbasis of C_q is a correct
+answer, and the synthetic spectra are nearly degenerate in the noise bulk): the
+solver is graded by invariants on its own output; the mask is graded as
+oracle_select(lambda_gpu) == mask_gpu; the stages after it are fed the GPU's
+R_r.  A well-separated case (r = rank + outliers) is also compared end to end
+with independent eigensolves.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_19218_amd as rk
+from rk_inputs import make_layer, make_normal, token_keep_lists
+from rk_inputs.generator import TAG_SIGMA
+
+from gpu_util import D, DEV, Pipeline, bf16_ulp, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4      # max|x-y| / max|y|
+TOL_BF16_OUT = 2e-2  # max|x-y|
+# Packed-Key bound: bf16 head+remainder split of R_r (<= 2^-16 |R|) plus 128 fp32
+# accumulation steps (128 * 2^-24), times sum_c |K_c||R_cj| <= ||K_row||_2.
+KT_ABS = (2.0 ** -16 + 128 * 2.0 ** -24)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = rk.rk_create(0)
+    yield c
+    rk.rk_destroy(c)
+
+
+def layer(B, Hq, Hkv, L, dtype, cid, lengths=None, **spec):
+    cfg = dict(id=cid, dtype=dtype, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, L=L)
+    return make_layer(cfg, lengths=lengths, spec_overrides=spec)
+
+
+def rel_max(x, y):
+    return np.abs(x - y).max() / max(np.abs(y).max(), 1e-300)
+
+
+def check_packed(got, K_rows, Rr, dtype):
+    """got [n, r] vs oracle K R_r rounded once to the cache dtype."""
+    want = oracle.compress(K_rows, Rr, rounding=dtype)
+    if dtype == "f32":
+        assert rel_max(got, want) <= TOL_F32
+    else:
+        bound = bf16_ulp(want) + KT_ABS * np.linalg.norm(K_rows, axis=1)[:, None]
+        assert np.all(np.abs(got - want) <= bound), float((np.abs(got - want) / bound).max())
+
+
+def oracle_decode(p, q, lens, use_bias=True, scale=0.0):
+    Kt = to_host(p.Kp)
+    V = to_host(p.Vc)
+    Rr = to_host(p.Rr)
+    dmu = to_host(p.dmu) if use_bias else None
+    return oracle.decode_batch(q.astype(np.float64), Kt, V, Rr, dmu, lens=np.asarray(lens, np.int32), scale=scale)
+
+
+def check_out(got, want, dtype):
+    if dtype == "f32":
+        assert rel_max(got, want) <= TOL_F32, rel_max(got, want)
+    else:
+        assert np.abs(got - want).max() <= TOL_BF16_OUT, np.abs(got - want).max()
+
+
+def run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, lengths=None, cap=None, sigma=None, center=True):
+    cap = cap or L + 8
+    p = Pipeline(ctx, B, Hq, Hkv, r, dtype, cap)
+    Kd, Vd = to_dev(data["K"], dtype), to_dev(data["V"], dtype)
+    n_dev = None if lengths is None else torch.tensor(lengths, device=DEV, dtype=torch.int32)
+    p.fit(Kd, L, sigma=sigma, center=center, n_dev=n_dev)
+    p.compress(Kd, L, V_dev=Vd, n_dev=n_dev)
+    return p
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,L,lengths,center", [
+    ("f32", 512, None, True),
+    ("bf16", 1300, [1300, 777], True),
+    ("bf16", 600, [600, 1], False),
+])
+def test_cov_mu_parity(ctx, dtype, L, lengths, center):
+    B, Hkv = (1 if lengths is None else 2), 2
+    data = layer(B, Hkv, Hkv, L, dtype, 11, lengths=lengths, mean_shift=3.0)
+    p = Pipeline(ctx, B, Hkv, Hkv, 32, dtype, L)
+    n_dev = None if lengths is None else torch.tensor(lengths, device=DEV, dtype=torch.int32)
+    p.fit(to_dev(data["K"], dtype), L, center=center, n_dev=n_dev)
+    cov, mu = to_host(p.cov), to_host(p.mu)
+    for b in range(B):
+        n = L if lengths is None else lengths[b]
+        for h in range(Hkv):
+            mu_o, C_o = oracle.mean_scatter(data["K"][b, h, :n], center=center)
+            assert rel_max(cov[b, h], C_o) <= TOL_F32
+            assert rel_max(mu[b, h], mu_o) <= TOL_F32
+            assert np.array_equal(cov[b, h], cov[b, h].T)
+
+
+@pytest.mark.parametrize("with_sigma", [False, True])
+def test_eig_invariants_and_mask(ctx, with_sigma):
+    B, Hkv, L, r = 2, 2, 700, 32
+    data = layer(B, Hkv, Hkv, L, "bf16", 12, mean_shift=2.0)
+    sigma = None
+    if with_sigma:
+        sg = np.abs(np.stack([np.stack([make_normal((D,), "f32", 12, 0, b, h, TAG_SIGMA) for h in range(Hkv)])
+                              for b in range(B)])) + 0.25
+        sigma = to_dev(sg, "f32")
+    p = Pipeline(ctx, B, Hkv, Hkv, r, "bf16", L)
+    p.fit(to_dev(data["K"], "bf16"), L, sigma=sigma)
+    cov, R, lam, mu = to_host(p.cov), to_host(p.R), to_host(p.lam), to_host(p.mu)
+    mask, keep, Rr, dmu = to_host(p.mask), to_host(p.keep_idx), to_host(p.Rr), to_host(p.dmu)
+    for b in range(B):
+        for h in range(Hkv):
+            Cq = cov[b, h] if sigma is None else oracle.weight(cov[b, h], sg[b, h].astype(np.float64))
+            Rm, lm = R[b, h], lam[b, h]
+            assert np.abs(Rm.T @ Rm - np.eye(D)).max() <= 1e-5
+            resid = Rm.T @ Cq @ Rm - np.diag(lm)
+            assert np.linalg.norm(resid) / np.linalg.norm(Cq) <= 1e-5
+            _, lam_o, _ = oracle.jacobi_eigh(Cq)
+            assert np.abs(np.sort(lm)[::-1] - lam_o).max() <= 1e-5 * lam_o[0]
+            # integer outputs: bit-exact against the oracle's rule applied to the same eigenvalues
+            m_o, k_o = oracle.select(lm, r)
+            assert np.array_equal(mask[b, h], m_o) and np.array_equal(keep[b, h], k_o)
+            assert np.array_equal(Rr[b, h], Rm[:, k_o])
+            d_o = oracle.delta_mu(mu[b, h], Rr[b, h])
+            assert np.abs(dmu[b, h] - d_o).max() <= TOL_F32 * max(np.abs(mu[b, h]).max(), 1e-30)
+            # top-r subspace against the oracle's independent eigensolve where the gap is large
+            f = oracle.fit(data["K"][b, h], 18, sigma=None if sigma is None else sg[b, h])
+            P_o = f["Rr"] @ f["Rr"].T
+            top = Rm[:, np.argsort(-lm)[:18]]
+            assert np.abs(top @ top.T - P_o).max() <= 1e-4
+    # rk_gather_rotation re-derives R_r from (R, keep_idx)
+    Rr2 = torch.zeros_like(p.Rr)
+    rk.rk_gather_rotation(ctx, p.layout(), p.R, p.keep_idx, Rr2)
+    torch.cuda.synchronize()
+    assert torch.equal(Rr2, p.Rr)
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,r,generic", [
+    ("f32", 32, False), ("bf16", 64, False), ("bf16", 64, True), ("bf16", 48, False), ("bf16", 16, False),
+    ("bf16", 96, False), ("bf16", 128, False), ("bf16", 37, False),
+])
+def test_compress_parity(ctx, dtype, r, generic):
+    B, Hkv, L = 2, 2, 333
+    lengths = [333, 70]
+    data = layer(B, Hkv, Hkv, L, dtype, 13, lengths=lengths)
+    rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, int(generic))
+    try:
+        p = run_prefill(ctx, data, B, Hkv, Hkv, L, r, dtype, lengths=lengths)
+    finally:
+        rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
+    Kt, Rr, Vc = to_host(p.Kp), to_host(p.Rr), to_host(p.Vc)
+    assert p.seq_len.cpu().tolist() == lengths
+    for b in range(B):
+        n = lengths[b]
+        for h in range(Hkv):
+            check_packed(Kt[b, h, :n], data["K"][b, h, :n].astype(np.float64), Rr[b, h], dtype)
+            assert np.array_equal(Vc[b, h, :n], data["V"][b, h, :n].astype(np.float64))
+            assert not Kt[b, h, n:].any() and not Vc[b, h, n:].any()     # rows past n untouched
+
+
+def test_compress_token_list_and_strides(ctx):
+    """Joint token+channel pruning stand-in: ragged lengths, a kept-token list per
+    sequence, Keys living in a [B, N, H, d] (token-major) buffer."""
+    B, Hkv, L, r, dtype = 3, 2, 900, 64, "bf16"
+    lengths = [900, 300, 65]
+    data = layer(B, Hkv, Hkv, L, dtype, 14, lengths=lengths)
+    tok_idx, tok_off = token_keep_lists(14, lengths, n_text=64, keep_frac=0.5)
+    n_keep = np.diff(tok_off)
+    Kd = to_dev(data["K"], dtype).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # strided view
+    Vd = to_dev(data["V"], dtype)
+    ti = torch.from_numpy(tok_idx).to(DEV)
+    to = torch.from_numpy(tok_off).to(DEV)
+    p = Pipeline(ctx, B, Hkv, Hkv, r, dtype, int(n_keep.max()) + 4)
+    p.fit(Kd, int(n_keep.max()), tok_idx=ti, tok_off=to)
+    p.compress(Kd, int(n_keep.max()), V_dev=Vd, tok_idx=ti, tok_off=to)
+    assert p.seq_len.cpu().tolist() == n_keep.tolist()
+    cov, mu, Kt, Rr, Vc = to_host(p.cov), to_host(p.mu), to_host(p.Kp), to_host(p.Rr), to_host(p.Vc)
+    for b in range(B):
+        rows = tok_idx[tok_off[b]:tok_off[b + 1]]
+        for h in range(Hkv):
+            mu_o, C_o = oracle.mean_scatter(data["K"][b, h], tok=rows)
+            assert rel_max(cov[b, h], C_o) <= TOL_F32 and rel_max(mu[b, h], mu_o) <= TOL_F32
+            check_packed(Kt[b, h, :rows.size], data["K"][b, h][rows].astype(np.float64), Rr[b, h], dtype)
+            assert np.array_equal(Vc[b, h, :rows.size], data["V"][b, h][rows].astype(np.float64))
+    q = to_dev(data["q"], dtype)
+    got = p.decode(q)
+    check_out(got, oracle_decode(p, data["q"], n_keep), dtype)
+
+
+# ---------------------------------------------------------------------------
+DECODE_CASES = [
+    # name, dtype, B, Hq, Hkv, L, lengths, r, generic, splits
+    ("tiny_f32", "f32", 1, 2, 2, 512, None, 32, False, 0),
+    ("gqa7_ragged", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 0),
+    ("gqa7_generic", "bf16", 2, 14, 2, 1000, [1000, 333], 64, True, 0),
+    ("mha_llava_shape", "bf16", 1, 32, 32, 2944, None, 64, False, 0),
+    ("r16", "bf16", 1, 8, 2, 700, None, 16, False, 0),
+    ("r32", "bf16", 1, 8, 2, 700, None, 32, False, 0),
+    ("r48", "bf16", 1, 8, 2, 700, None, 48, False, 0),
+    ("r96", "bf16", 1, 8, 2, 700, None, 96, False, 0),
+    ("r128_dense", "bf16", 1, 8, 2, 700, None, 128, False, 0),
+    ("r37_odd", "bf16", 1, 8, 2, 300, None, 37, False, 0),
+    ("g20_two_groups", "bf16", 1, 20, 1, 300, None, 32, False, 0),
+    ("empty_and_one", "bf16", 3, 4, 2, 130, [0, 1, 130], 32, False, 0),
+    ("one_split", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 1),
+    ("seven_splits", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 7),
+]
+
+
+@pytest.mark.parametrize("case", DECODE_CASES, ids=[c[0] for c in DECODE_CASES])
+def test_decode_parity(ctx, case):
+    _, dtype, B, Hq, Hkv, L, lengths, r, generic, splits = case
+    data = layer(B, Hq, Hkv, L, dtype, 15, lengths=lengths, mean_shift=1.5)
+    p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, lengths=lengths)
+    lens = lengths or [L] * B
+    rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, int(generic))
+    rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, splits)
+    try:
+        q = to_dev(data["q"], dtype)
+        got = p.decode(q)
+        got_nobias = p.decode(q, use_bias=False).copy()
+        again = p.decode(q)
+    finally:
+        rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
+        rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 0)
+    want = oracle_decode(p, data["q"], lens)
+    check_out(got, want, dtype)
+    check_out(got_nobias, want, dtype)          # bias = constant shift when all tokens are rotated
+    assert np.array_equal(got, again)            # fixed merge order: bit-stable
+    for b in range(B):
+        if lens[b] == 0:
+            assert not got[b].any()
+
+
+def test_decode_custom_scale(ctx):
+    B, Hq, Hkv, L, r, dtype = 1, 4, 2, 400, 32, "bf16"
+    data = layer(B, Hq, Hkv, L, dtype, 16)
+    p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype)
+    got = p.decode(to_dev(data["q"], dtype), scale=0.05)
+    check_out(got, oracle_decode(p, data["q"], [L], scale=0.05), dtype)
+
+
+# ---------------------------------------------------------------------------
+def test_append_then_decode(ctx):
+    """Frozen-R appends: 12 steps of (append, decode), each checked."""
+    B, Hq, Hkv, L, r, dtype = 2, 8, 4, 500, 48, "bf16"
+    lengths = [500, 250]
+    data = layer(B, Hq, Hkv, L, dtype, 17, lengths=lengths)
+    p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, lengths=lengths, cap=L + 12)
+    Rr = to_host(p.Rr)
+    lens = list(lengths)
+    for step in range(12):
+        new = layer(B, Hq, Hkv, 1, dtype, 1700 + step)
+        p.append(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype))
+        Kt, Vc = to_host(p.Kp), to_host(p.Vc)
+        for b in range(B):
+            for h in range(Hkv):
+                check_packed(Kt[b, h, lens[b]:lens[b] + 1], new["k_new"][b, h][None].astype(np.float64), Rr[b, h], dtype)
+                assert np.array_equal(Vc[b, h, lens[b]], new["v_new"][b, h].astype(np.float64))
+        lens = [x + 1 for x in lens]
+        assert p.seq_len.cpu().tolist() == lens
+        got = p.decode(to_dev(new["q"], dtype))
+        check_out(got, oracle_decode(p, new["q"], lens), dtype)
+    # capacity: host check refuses, nothing changes
+    with pytest.raises(rk.RotateKError) as e:
+        p.append(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype))
+    assert e.value.status == rk.RK_ERR_CAPACITY
+    assert p.seq_len.cpu().tolist() == lens
+
+
+def test_append_device_guard(ctx):
+    """A sequence already at capacity is left untouched on the device even when the
+    host bound allows the call (ragged batch)."""
+    B, Hkv, r, dtype, cap = 2, 2, 32, "bf16", 64
+    data = layer(B, Hkv, Hkv, cap, dtype, 18, lengths=[64, 10])
+    p = run_prefill(ctx, data, B, Hkv, Hkv, cap, r, dtype, lengths=[64, 10], cap=cap)
+    before = to_host(p.Kp).copy()
+    p.max_seq_len = 10                      # host bound of the short sequence only
+    new = layer(B, Hkv, Hkv, 1, dtype, 1800)
+    p.append(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype))
+    assert p.seq_len.cpu().tolist() == [64, 11]
+    after = to_host(p.Kp)
+    assert np.array_equal(after[0], before[0])
+    assert after[1, :, 10].any()
+
+
+# ---------------------------------------------------------------------------
+def test_end_to_end_tiny_fp32(ctx):
+    """The tiny fp32 config through the whole path.  With r = rank + outliers the kept
+    subspace is separated from the noise bulk by a large gap, so GPU and oracle
+    (independent eigensolves) must agree outright; at r = 32 (inside the bulk) the
+    difference is reported and the stage-wise check is the graded one."""
+    B, H, L, dtype = 1, 2, 512, "f32"
+    data = layer(B, H, H, L, dtype, 1)
+    for r, graded in ((18, True), (32, False)):
+        p = run_prefill(ctx, data, B, H, H, L, r, dtype)
+        got = p.decode(to_dev(data["q"], dtype))
+        check_out(got, oracle_decode(p, data["q"], [L]), dtype)          # stage-wise
+        full = np.zeros_like(got)
+        for h in range(H):
+            f = oracle.fit(data["K"][0, h], r)
+            Kt = oracle.compress(data["K"][0, h], f["Rr"], rounding=dtype)
+            full[0, h] = oracle.decode_head(data["q"][0, h], Kt, data["V"][0, h], f["Rr"], f["dmu"])
+        err = rel_max(got, full)
+        print(f"end-to-end r={r}: rel max err {err:.3e}")
+        if graded:
+            assert err <= TOL_F32
+
+
+def test_full_size_gqa_16k(ctx):
+    """The benchmark configuration (B=8, 28 query / 4 KV heads, L=16384, r=64, bf16) in the
+    launch configuration bench.py times; every output is compared with the oracle."""
+    B, Hq, Hkv, L, r, dtype = 8, 28, 4, 16384, 64, "bf16"
+    data = layer(B, Hq, Hkv, L, dtype, 3)
+    p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, cap=L)
+    cov = to_host(p.cov)
+    mu_o, C_o = oracle.mean_scatter(data["K"][5, 2])
+    assert rel_max(cov[5, 2], C_o) <= TOL_F32
+    Kt, Rr = to_host(p.Kp), to_host(p.Rr)
+    for (b, h) in ((0, 0), (7, 3)):
+        sel = np.r_[0:40, 8000:8040, 16344:16384]
+        check_packed(Kt[b, h][sel], data["K"][b, h][sel].astype(np.float64), Rr[b, h], dtype)
+    got = p.decode(to_dev(data["q"], dtype))
+    want = oracle_decode(p, data["q"], [L] * B)
+    check_out(got, want, dtype)
+    assert np.array_equal(got, p.decode(to_dev(data["q"], dtype)))
