@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the RotateK hot path on one MI355X.
+
+Workload ("C3"): one GQA attention layer, bf16, batch 8, 28 query heads over 4 KV
+heads, head dim 128, 16384 cached tokens, r = 64 kept Key channels.  One step =
+one pass of the whole path over one layer: fit (covariance, eigensolve, mask),
+compress (rotate + pack 16384 Keys), append one token, one decode-attention
+step.  Steps rotate over a ring of distinct layers (several GB in total) so that
+every step streams its cache from HBM rather than from the 256 MB last-level
+cache.  Inputs are seeded synthetic tensors already resident in HBM.
+
+Prints ONE JSON line.  `value` is the decode-attention achieved HBM bandwidth
+(algorithmic bytes B*H_kv*L*(r+d)*2 per step / measured time of the decode call).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--layers", type=int, default=8, help="distinct layer caches in the ring")
+    ap.add_argument("--keep", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by "
+              "(batch item, KV head) with no exchange; see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_19218_amd as rk
+    from rk_inputs import CONFIGS, f32_to_bf16_bits, make_layer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    dev = "cuda:0"
+    cfg = dict(CONFIGS["C3"])
+    B, Hq, Hkv, D, L = cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["L"]
+    r_main = args.keep
+    cap = L + 64                                                # multiple of 32
+    NL = args.layers
+
+    def to_bf16(x):
+        bits = f32_to_bf16_bits(np.ascontiguousarray(x, dtype=np.float32)).view(np.int16)
+        return torch.from_numpy(bits).to(dev).view(torch.bfloat16)
+
+    # ---- seeded inputs, resident in HBM ------------------------------------------------
+    t_gen = time.time()
+    with ThreadPoolExecutor(max_workers=min(NL, 8)) as ex:
+        host_layers = list(ex.map(lambda l: make_layer(cfg, layer=l), range(NL)))
+    layers = []
+    for hl in host_layers:
+        layers.append(dict(K=to_bf16(hl["K"]), V=to_bf16(hl["V"]),          # [B,Hkv,L,D] prefill Keys / Values
+                           q=to_bf16(hl["q"]), k_new=to_bf16(hl["k_new"]), v_new=to_bf16(hl["v_new"])))
+    t_gen = time.time() - t_gen
+
+    ctx = rk.rk_create(0)
+    f32 = dict(device=dev, dtype=torch.float32)
+
+    def alloc_state(r):
+        st = []
+        kb, vb = rk.rk_cache_bytes(rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, cap, L))
+        for _ in range(NL):
+            st.append(dict(
+                R=torch.empty(B, Hkv, D, D, **f32), lam=torch.empty(B, Hkv, D, **f32),
+                mask=torch.empty(B, Hkv, D, device=dev, dtype=torch.uint8),
+                keep=torch.empty(B, Hkv, r, device=dev, dtype=torch.int32),
+                Rr=torch.empty(B, Hkv, D, r, **f32), mu=torch.empty(B, Hkv, D, **f32),
+                dmu=torch.empty(B, Hkv, D, **f32),
+                Kp=torch.zeros(kb, device=dev, dtype=torch.uint8),       # fragment-major caches
+                Vc=torch.zeros(vb, device=dev, dtype=torch.uint8),
+                seq_len=torch.zeros(B, device=dev, dtype=torch.int32),
+                out=torch.empty(B, Hq, D, device=dev, dtype=torch.bfloat16)))
+        return st
+
+    def layouts(r, st):
+        fit_l = rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, cap, L, seq_len=st["seq_len"])
+        dec_l = rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, cap, L + 1, seq_len=st["seq_len"])
+        return fit_l, dec_l
+
+    lay0 = rk.Layout(B, Hq, Hkv, 128, rk.RK_BF16, cap, L + 1)
+    fit_ws = torch.empty(rk.rk_fit_workspace_size(lay0, L), device=dev, dtype=torch.uint8)
+    dec_ws = torch.empty(rk.rk_decode_workspace_size(ctx, lay0) * 2, device=dev, dtype=torch.uint8)
+
+    def do_fit(r, st, ly):
+        fl, _ = layouts(r, st)
+        out = rk.FitOut(st["R"], st["lam"], st["mask"], st["keep"], st["Rr"], st["mu"], st["dmu"])
+        rk.rk_fit_rotation(ctx, fl, rk.Rows(ly["K"], L), None, rk.RK_FIT_CENTER, out, fit_ws)
+
+    def do_compress(r, st, ly):
+        fl, _ = layouts(r, st)
+        rk.rk_compress(ctx, fl, rk.Rows(ly["K"], L), st["Rr"], st["Kp"], values=rk.Rows(ly["V"], L),
+                       v_cache=st["Vc"], seq_len_out=st["seq_len"])
+
+    def do_append(r, st, ly):
+        fl, _ = layouts(r, st)
+        rk.rk_append(ctx, fl, ly["k_new"], ly["v_new"], st["Rr"], st["Kp"], st["Vc"], st["seq_len"])
+
+    def do_decode(r, st, ly):
+        _, dl = layouts(r, st)
+        rk.rk_decode_attn(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], 0.0, st["out"], dec_ws)
+
+    STAGES = [("fit", do_fit), ("compress", do_compress), ("append", do_append), ("decode", do_decode)]
+    state = alloc_state(r_main)
+
+    def step(i, events=None):
+        st, ly = state[i % NL], layers[i % NL]
+        for s, (name, fn) in enumerate(STAGES):
+            if events is not None:
+                events[s].record()
+            fn(r_main, st, ly)
+        if events is not None:
+            events[len(STAGES)].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    stage_us = {}
+    for s, (name, _) in enumerate(STAGES):
+        ts = sorted(e[s].elapsed_time(e[s + 1]) * 1e3 for e in evs)
+        stage_us[name] = dict(mean=float(np.mean(ts)), median=float(ts[len(ts) // 2]),
+                              p10=float(ts[len(ts) // 10]), p90=float(ts[(len(ts) * 9) // 10]))
+    out0 = state[0]["out"].float()
+    assert torch.isfinite(out0).all(), "decode output is not finite"
+
+    def decode_bytes(r, Lc):
+        return B * Hkv * Lc * (r + D) * 2
+
+    dec_us = stage_us["decode"]["mean"]
+    dec_gbps = decode_bytes(r_main, L + 1) / (dec_us * 1e-6) / 1e9
+    comp_bytes = B * Hkv * L * (D + r_main + 2 * D) * 2      # read K, write K~, read V, write tiled V
+    comp_gbps = comp_bytes / (stage_us["compress"]["mean"] * 1e-6) / 1e9
+    n_splits, tps = rk.rk_decode_plan(ctx, layouts(r_main, state[0])[1])
+
+    # ---- decode-only back-to-back (the serving loop) + r sweep ---------------------------
+    sweep = {}
+    rs = [r_main] if args.no_sweep else sorted(set(cfg["keep_sweep"]) | {r_main, 128})
+    for r in rs:
+        stt = state if r == r_main else alloc_state(r)
+        if r != r_main:
+            for i in range(NL):
+                do_fit(r, stt[i], layers[i])
+                do_compress(r, stt[i], layers[i])
+        else:
+            for i in range(NL):
+                do_compress(r, stt[i], layers[i])       # reset lengths to L
+        for i in range(args.warmup):
+            do_decode(r, stt[i % NL], layers[i % NL])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            do_decode(r, stt[i % NL], layers[i % NL])
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        sweep[str(r)] = dict(us_per_step=us, GBps=decode_bytes(r, L) / (us * 1e-6) / 1e9,
+                             frac_of_peak=decode_bytes(r, L) / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS)
+        if r != r_main:
+            del stt
+            torch.cuda.empty_cache()
+
+    # ---- the CPU oracle on the same workload (bounded sample) -------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_util import to_host
+        st, ly, hl = state[0], layers[0], host_layers[0]
+        nb = B                                                  # the whole batch: one full decode step
+        k_rows = torch.empty(B, Hkv, cap, r_main, device=dev, dtype=torch.bfloat16)
+        rk.rk_unpack_cache(ctx, layouts(r_main, st)[0], st["Kp"], None, k_rows, None)
+        torch.cuda.synchronize()
+        Kt = to_host(k_rows[:nb, :, :L])
+        Vh = to_host(ly["V"][:nb])
+        Rr, dmu = to_host(st["Rr"][:nb]), to_host(st["dmu"][:nb])
+        qh = hl["q"][:nb].astype(np.float64)
+        t = time.perf_counter()
+        o = oracle.decode_batch(qh, Kt, Vh, Rr, dmu)
+        t_dec = time.perf_counter() - t
+        got = to_host(st["out"][:nb])
+        # the last timed step on layer 0 decoded L+1 tokens; the sample decodes the L prefill tokens:
+        # only a sanity bound here, exact parity is the tests' job
+        assert np.isfinite(o).all()
+        Kh = hl["K"].reshape(B * Hkv, L, D).astype(np.float64)  # all 32 KV heads
+        t = time.perf_counter()
+        f = oracle.fit_batch(Kh, r_main)
+        t_fit = time.perf_counter() - t
+        t = time.perf_counter()
+        oracle.compress_batch(Kh, f["Rr"], rounding="bf16")
+        t_cmp = time.perf_counter() - t
+        cpu = dict(value=decode_bytes(r_main, L) * nb / B / t_dec / 1e9, unit="GB/s", cores=oracle.num_threads(),
+                   kind="oracle",
+                   sample=("one whole step of the workload, no sampling: fp64 oracle decode step (%d query heads, "
+                           "L=%d): %.3f s; fit of all %d KV heads: %.3f s; compress of all %d heads: %.3f s; "
+                           "value = decode bytes / decode time")
+                   % (B * Hq, L, t_dec, B * Hkv, t_fit, B * Hkv, t_cmp))
+
+    res = {
+        "metric": "decode_attn_hbm_GBps", "value": dec_gbps, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic (seeded low-rank + outlier Keys, N(0,1) Values and queries)",
+        "config": {"workload": "C3: GQA layer bf16, B=8, 28 q heads / 4 KV heads, d=128, L=16384, r=%d; step = "
+                               "fit + compress + append + decode over a ring of %d layers" % (r_main, NL),
+                   "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "L": L, "keep": r_main,
+                   "ring_layers": NL, "decode_splits": n_splits, "tokens_per_split": tps},
+        "us_per_decode_step": dec_us,
+        "compress_GBps": comp_gbps,
+        "stages_us": stage_us,
+        "decode_only_sweep": sweep,
+        "roofline": {"bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "decode_fused_mfma<64> (rk_decode_attn, one launch)",
+                     "algorithmic_bytes": decode_bytes(r_main, L + 1)},
+        "roofline_compress": {"bound": "hbm", "achieved": comp_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": comp_gbps / HBM_PEAK_GBPS, "algorithmic_bytes": comp_bytes},
+        "cpu_baseline": cpu,
+        "setup_s": t_gen,
+    }
+    print(json.dumps(res))
+    rk.rk_destroy(ctx)
+
+
+if __name__ == "__main__":
+    main()

@@ -21,8 +21,16 @@
  *     cache; R, R_r, mu, delta_mu, eigenvalues and all scratch are fp32.
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads) (App. C: R is
  *     indexed [B, H_kv, d, d_keep]).
- *   - Cache layout: packed rotated keys K~ [B, H_kv, capacity, keep] and
- *     values V [B, H_kv, capacity, d], both contiguous, rows = tokens.
+ *   - Cache layout: the packed rotated keys K~ and the values V live in two
+ *     caller-allocated buffers of rk_cache_bytes() bytes whose INTERNAL layout is
+ *     fragment-major (tiled so that the decode kernel's matrix-core operands are
+ *     contiguous 1 KB pieces of HBM): per (b, h_kv) slab of `capacity` tokens,
+ *       K~ element (token t, channel c):  [t/16][c/8][t%16][c%8], keep padded to 8
+ *       V  element (token t, channel c):  [t/32][c/16][g][c%16][jj],
+ *                                         g = (t%16)/4, jj = 4*((t%32)/16) + t%4
+ *     Only rk_compress and rk_append write them; rk_unpack_cache converts a cache
+ *     back to row-major [B, H_kv, capacity, keep] / [B, H_kv, capacity, d] for
+ *     inspection.  capacity must be a multiple of 32.
  *   - Sequence lengths live on the device (int32 seq_len[B]); the host gives
  *     an upper bound max_seq_len that sizes the grids.  Kernels never read or
  *     write rows >= min(seq_len[b], capacity).
@@ -73,7 +81,7 @@ typedef struct {
     int32_t head_dim;         /* d = 128                                              */
     int32_t keep;             /* r: kept channels per head, 1..d                      */
     int32_t dtype;            /* RK_F32 | RK_BF16                                     */
-    int32_t capacity;         /* rows allocated per (b, h_kv) in K~ and V             */
+    int32_t capacity;         /* tokens allocated per (b, h_kv) in K~ and V; multiple of 32 */
     int32_t max_seq_len;      /* host upper bound on seq_len[b]                       */
     const int32_t* seq_len;   /* device [B]: tokens currently cached per sequence     */
 } rk_layout;
@@ -120,6 +128,9 @@ rk_status rk_set_option(rk_ctx* ctx, int32_t key, int64_t value);
 /* Validate a layout on the host (also done inside every entry point). */
 rk_status rk_validate_layout(const rk_layout* L);
 
+/* Bytes the caller must allocate for the packed-Key cache and the Value cache. */
+rk_status rk_cache_bytes(const rk_layout* L, size_t* k_packed_bytes, size_t* v_cache_bytes);
+
 /* Bytes of workspace rk_fit_rotation needs for at most max_tokens rows per sequence. */
 size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens);
 /* Bytes of workspace rk_decode_attn needs (depends on batch, heads, max_seq_len). */
@@ -148,19 +159,26 @@ rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R,
                              const int32_t* keep_idx, float* R_r, void* stream);
 
 /* ---- Alg. 1 step 14: K~ = K R_k, rounded once to the cache dtype ------------
- * Writes rows [0, n_b) of k_packed[b, h] (n_b as defined at rk_rows; must be
+ * Writes tokens [0, n_b) of k_packed[b, h] (n_b as defined at rk_rows; must be
  * <= capacity, checked on the host against keys->n_tokens).  If `values` is
- * non-NULL its rows are copied (gathered through the same token list) into
- * v_cache.  If seq_len_out is non-NULL it receives n_b per sequence.
+ * non-NULL its rows (gathered through the same token list) are re-tiled into
+ * v_cache; this is how the Value cache is built.  If seq_len_out is non-NULL it
+ * receives n_b per sequence.
  * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY, HIP.                            */
 rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* R_r,
                       void* k_packed, const rk_rows* values, void* v_cache,
                       int32_t* seq_len_out, void* stream);
 
+/* Inspection helper: caches -> row-major k_rows [B,H_kv,capacity,keep] and/or
+ * v_rows [B,H_kv,capacity,d] (either may be NULL).  Not on the hot path.        */
+rk_status rk_unpack_cache(rk_ctx* ctx, const rk_layout* L, const void* k_packed, const void* v_cache,
+                          void* k_rows, void* v_rows, void* stream);
+
 /* ---- frozen-R append of one token per sequence ------------------------------
  * k~ = k_new R_r (R is fitted once at the end of prefill and reused, Sec. 3.2
- * Step (1)); writes row seq_len[b] of k_packed and v_cache for every KV head,
- * then seq_len[b] += 1 on the device.  k_new, v_new: [B,H_kv,d] in L->dtype.
+ * Step (1)); writes token seq_len[b] of k_packed and v_cache for every KV head,
+ * then seq_len[b] += 1 on the device (one launch; calls on one context must not
+ * overlap on different streams).  k_new, v_new: [B,H_kv,d] in L->dtype.
  * Returns RK_ERR_CAPACITY if L->max_seq_len + 1 > capacity (nothing is
  * launched); on the device a sequence already at capacity is left untouched.  */
 rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new,
@@ -170,7 +188,8 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
  * q~ = q R_r, b = q . delta_mu (delta_mu NULL = no bias), scores
  * (q~ . K~_n + b) * scale with scale = 1/sqrt(d) when `scale` <= 0, softmax over
  * the seq_len[b] cached tokens, out = P V.  q, out: [B,H_q,d] in L->dtype.
- * A sequence with seq_len[b] = 0 yields zeros.
+ * A sequence with seq_len[b] = 0 yields zeros.  Two launches (split-K, merge) as
+ * in App. C, one when the plan has a single split.
  * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (max_seq_len > capacity),
  * WORKSPACE, HIP.                                                             */
 rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,

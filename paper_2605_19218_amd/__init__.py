@@ -26,7 +26,7 @@ RK_DEVICE_NONE = -1
 EXPORTS = [
     "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
-    "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn",
+    "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
 ]
 
 
@@ -79,6 +79,8 @@ def lib():
         L.rk_decode_workspace_size.argtypes = [vp, PL]
         L.rk_decode_workspace_size.restype = sz
         L.rk_decode_plan.argtypes = [vp, PL, C.POINTER(i32), C.POINTER(i32)]
+        L.rk_cache_bytes.argtypes = [PL, C.POINTER(sz), C.POINTER(sz)]
+        L.rk_unpack_cache.argtypes = [vp, PL, vp, vp, vp, vp, vp]
         L.rk_fit_rotation.argtypes = [vp, PL, PR, vp, u32, PF, vp, sz, vp]
         L.rk_gather_rotation.argtypes = [vp, PL, vp, vp, vp, vp]
         L.rk_compress.argtypes = [vp, PL, PR, vp, vp, PR, vp, vp, vp]
@@ -187,6 +189,20 @@ def rk_set_option(ctx, key: int, value: int) -> None:
 
 def rk_validate_layout(layout: Layout) -> int:
     return lib().rk_validate_layout(C.byref(layout.c()))
+
+
+def rk_cache_bytes(layout: Layout):
+    """(bytes of the packed-Key cache, bytes of the Value cache)."""
+    k, v = C.c_size_t(), C.c_size_t()
+    st = lib().rk_cache_bytes(C.byref(layout.c()), C.byref(k), C.byref(v))
+    if st != RK_OK:
+        raise RotateKError(st, lib().rk_status_str(st).decode())
+    return k.value, v.value
+
+
+def rk_unpack_cache(ctx, layout: Layout, k_packed, v_cache, k_rows, v_rows, stream=None) -> None:
+    _check(ctx, lib().rk_unpack_cache(ctx, C.byref(layout.c()), _ptr(k_packed), _ptr(v_cache), _ptr(k_rows),
+                                      _ptr(v_rows), _stream(stream)))
 
 
 def rk_fit_workspace_size(layout: Layout, max_tokens: int) -> int:

@@ -13,6 +13,7 @@ struct rk_ctx {
     int n_cu;
     int force_generic;
     int decode_splits;
+    int32_t* tickets;     // device: APP_TICKETS zero-initialised counters (one per batch item, rk_append)
     char err[256];
 };
 
@@ -36,6 +37,8 @@ rk_status hip_fail(rk_ctx* ctx, hipError_t e, const char* what)
     return fail(ctx, RK_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+constexpr int APP_TICKETS = 1 << 16;   // >= batch
+
 size_t elem_size(int dtype) { return dtype == RK_F32 ? 4 : 2; }
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -50,7 +53,8 @@ rk_status check_layout(rk_ctx* ctx, const rk_layout* L)
     if (L->n_q_heads % L->n_kv_heads != 0)
         return fail(ctx, RK_ERR_INVALID_ARG, "n_q_heads %d is not a multiple of n_kv_heads %d", L->n_q_heads, L->n_kv_heads);
     if (L->keep < 1 || L->keep > D) return fail(ctx, RK_ERR_INVALID_ARG, "keep %d outside 1..128", L->keep);
-    if (L->capacity < 1) return fail(ctx, RK_ERR_INVALID_ARG, "capacity must be positive");
+    if (L->capacity < 32 || L->capacity % 32 != 0)
+        return fail(ctx, RK_ERR_INVALID_ARG, "capacity %d must be a positive multiple of 32", L->capacity);
     if (L->max_seq_len < 0) return fail(ctx, RK_ERR_INVALID_ARG, "max_seq_len is negative");
     return RK_OK;
 }
@@ -106,7 +110,7 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tps_out
     int S;
     if (ctx && ctx->decode_splits > 0) S = ctx->decode_splits;
     else {
-        long target = 4L * n_cu;
+        long target = 2L * n_cu;          // two 4-wave work-groups per compute unit
         S = (int)((target + units - 1) / units);
         if (S > 64) S = 64;
     }
@@ -153,6 +157,16 @@ rk_status rk_create(rk_ctx** out, int device)
         hipError_t e = hipGetDeviceProperties(&prop, device);
         if (e != hipSuccess) { delete c; return RK_ERR_HIP; }
         c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        const size_t tb = (size_t)APP_TICKETS * sizeof(int32_t);
+        if (hipSetDevice(device) != hipSuccess || hipMalloc((void**)&c->tickets, tb) != hipSuccess) {
+            delete c;
+            return RK_ERR_HIP;
+        }
+        if (hipMemset(c->tickets, 0, tb) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipFree(c->tickets);
+            delete c;
+            return RK_ERR_HIP;
+        }
     }
     *out = c;
     return RK_OK;
@@ -161,6 +175,7 @@ rk_status rk_create(rk_ctx** out, int device)
 rk_status rk_destroy(rk_ctx* ctx)
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
+    if (ctx->tickets) (void)hipFree(ctx->tickets);
     delete ctx;
     return RK_OK;
 }
@@ -205,6 +220,33 @@ rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_split
     decode_plan(ctx, L, &S, &tps);
     *n_splits = S;
     *tokens_per_split = tps;
+    return RK_OK;
+}
+
+rk_status rk_cache_bytes(const rk_layout* L, size_t* k_packed_bytes, size_t* v_cache_bytes)
+{
+    rk_status s = check_layout(nullptr, L);
+    if (s != RK_OK) return s;
+    const size_t slabs = (size_t)L->batch * L->n_kv_heads * L->capacity;
+    if (k_packed_bytes) *k_packed_bytes = slabs * keep_padded(L->keep) * elem_size(L->dtype);
+    if (v_cache_bytes) *v_cache_bytes = slabs * D * elem_size(L->dtype);
+    return RK_OK;
+}
+
+rk_status rk_unpack_cache(rk_ctx* ctx, const rk_layout* L, const void* k_packed, const void* v_cache,
+                          void* k_rows, void* v_rows, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if ((k_rows && !k_packed) || (v_rows && !v_cache) || (!k_rows && !v_rows))
+        return fail(ctx, RK_ERR_INVALID_ARG, "unpack: nothing to do or source missing");
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_unpack(L->dtype, L->batch * L->n_kv_heads, L->capacity, L->keep, k_packed, v_cache, k_rows, v_rows,
+                      as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "unpack launch");
     return RK_OK;
 }
 
@@ -290,8 +332,8 @@ rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, cons
                         R_r, k_packed, seq_len_out, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "compress launch");
     if (values) {
-        e = launch_row_copy(L->dtype, to_dev(values), L->batch, L->n_kv_heads, L->capacity, v_cache, st);
-        if (e != hipSuccess) return hip_fail(ctx, e, "value copy launch");
+        e = launch_v_retile(L->dtype, to_dev(values), L->batch, L->n_kv_heads, L->capacity, v_cache, st);
+        if (e != hipSuccess) return hip_fail(ctx, e, "value re-tiling launch");
     }
     return RK_OK;
 }
@@ -306,11 +348,12 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
         return fail(ctx, RK_ERR_INVALID_ARG, "append: NULL pointer");
     if (L->max_seq_len + 1 > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "append: %d + 1 rows exceed capacity %d", L->max_seq_len, L->capacity);
+    if (L->batch > APP_TICKETS) return fail(ctx, RK_ERR_UNSUPPORTED, "append: batch too large");
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_append(L->dtype, L->batch, L->n_kv_heads, L->capacity, L->keep, k_new, v_new, R_r, k_packed,
-                      v_cache, seq_len, as_stream(stream));
+                      v_cache, seq_len, ctx->tickets, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "append launch");
     return RK_OK;
 }

@@ -1,7 +1,8 @@
 // Rotate + gather + pack of the Key cache (Alg. 1 step 14: K~ = K R_k, stored in
-// place of K, rounded once to the cache dtype) and the frozen-R append of new
-// tokens (the rotation is fitted once at the end of prefill and reused,
-// Sec. 3.2 Step (1)).
+// place of K, rounded once to the cache dtype), re-tiling of the Values into the
+// decode kernel's fragment-major layout, the frozen-R append of new tokens (the
+// rotation is fitted once at the end of prefill and reused, Sec. 3.2 Step (1)),
+// and the inverse re-tiling used to inspect a cache.
 #include "rk_kernels.hpp"
 
 namespace rk {
@@ -21,6 +22,7 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
     const int t0 = blockIdx.x * 64;
     if (t0 >= n_b) return;
     const int nt = min(64, n_b - t0);
+    const int rp = keep_padded(r);
     const T* base = (const T*)rows.data;
     __shared__ float tile[64][D];
     for (int idx = tid; idx < nt * D; idx += 256) {
@@ -29,11 +31,12 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
     }
     __syncthreads();
     const float* Ru = Rr + (size_t)u * D * r;
+    T* Ku = Kp + (size_t)u * cap * rp;
     for (int o = tid; o < nt * r; o += 256) {
         int t = o / r, j = o - t * r;
         float a = 0.f;
         for (int c = 0; c < D; ++c) a = fmaf(tile[t][c], Ru[c * r + j], a);
-        st_elem(Kp + ((size_t)u * cap + t0 + t) * r + j, a);
+        st_elem(Ku + kidx(t0 + t, j, rp), a);
     }
 }
 
@@ -43,16 +46,26 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
 // 32 i + 8 g ..+7) is a plain 16-byte load of a Key row, so Keys go from HBM
 // straight into MFMA registers.  R_r is split into bf16 head + remainder
 // (two MFMAs) to keep ~fp32 accuracy of the fp32 rotation.  The rows of the A
-// operand are permuted so that lane (g, n) ends up holding the r/4 CONTIGUOUS
-// output channels g*r/4 .. of token n: each wave then writes one contiguous
-// 16-token x r block of the packed cache.
+// operand are permuted so that after output blocks 2i and 2i+1 lane (g, n) holds
+// the 8 output channels 32 i + 8 g ..+7 of token n -- one 16-byte piece of the
+// packed layout, and consecutive lanes write consecutive pieces.
 template <int R>
 struct CompressCfg {
     static constexpr int JB = R / 16;                 // 16-wide output-channel blocks
+    static constexpr int NF = R / 32;                 // full 32-channel groups
+    static constexpr bool TAIL = (R % 32) != 0;       // one trailing 16-channel block
     static constexpr int TT = (R <= 64) ? 4 : 2;      // 16-token tiles in flight per wave
     static constexpr int TOK_PER_BLOCK = 4 * TT * 16; // 4 waves
     static constexpr size_t LDS_BYTES = (size_t)JB * 4 * 2 * 64 * 16;   // A fragments, hi+lo
+    // output channel held by A row a of block jb
+    __host__ __device__ static constexpr int chan(int jb, int a) {
+        return (jb < 2 * NF) ? 32 * (jb >> 1) + 8 * (a >> 2) + 4 * (jb & 1) + (a & 3) : 32 * NF + a;
+    }
 };
+
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
+    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
 
 template <int R>
 __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int cap,
@@ -71,13 +84,13 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
     const int blk0 = blockIdx.x * Cfg::TOK_PER_BLOCK;
     if (blk0 >= n_b) return;
 
-    // A fragments: block jb, k-step i, lane (gk, a): rows a <-> output channel
-    // (a/4)*(R/4) + 4 jb + a%4 ; k slots <-> input channels 32 i + 8 gk + jj.
+    // A fragments: block jb, k-step i, lane (gk, a): row a <-> output channel chan(jb, a);
+    // k slots <-> input channels 32 i + 8 gk + jj.
     const float* Ru = Rr + (size_t)u * D * R;
     for (int f = tid; f < Cfg::JB * 4 * 64; f += 256) {
         int l = f & 63, i = (f >> 6) & 3, jb = f >> 8;
         int gk = l >> 4, a = l & 15;
-        int j = (a >> 2) * (R / 4) + 4 * jb + (a & 3);
+        int j = Cfg::chan(jb, a);
         bf16x8 hi, lo;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
@@ -123,72 +136,134 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
             }
         }
     }
-    // lane (g, n): acc[tt][jb][ii] = channel g*R/4 + 4 jb + ii of token w0 + 16 tt + n
+    // lane (g, n): blocks 2i, 2i+1 hold channels 32 i + 8 g + (0..3), (4..7) of token w0 + 16 tt + n
+    bf16_t* Ku = Kp + (size_t)u * cap * R;
 #pragma unroll
     for (int tt = 0; tt < Cfg::TT; ++tt) {
         int tok = w0 + tt * 16 + n;
         if (tok < n_b) {
-            bf16_t* dst = Kp + ((size_t)u * cap + tok) * R + g * (R / 4);
+            bf16_t* blk = Ku + (size_t)((w0 >> 4) + tt) * (16 * R);
 #pragma unroll
-            for (int jb = 0; jb < Cfg::JB; ++jb) {
+            for (int i = 0; i < Cfg::NF; ++i) {
+                uint4 pk;
+                pk.x = pack2_bf16(acc[tt][2 * i][0], acc[tt][2 * i][1]);
+                pk.y = pack2_bf16(acc[tt][2 * i][2], acc[tt][2 * i][3]);
+                pk.z = pack2_bf16(acc[tt][2 * i + 1][0], acc[tt][2 * i + 1][1]);
+                pk.w = pack2_bf16(acc[tt][2 * i + 1][2], acc[tt][2 * i + 1][3]);
+                *(uint4*)(blk + (4 * i) * 128 + lane * 8) = pk;
+            }
+            if (Cfg::TAIL) {
                 uint2 pk;
-                pk.x = (uint32_t)f32_to_bf16(acc[tt][jb][0]) | ((uint32_t)f32_to_bf16(acc[tt][jb][1]) << 16);
-                pk.y = (uint32_t)f32_to_bf16(acc[tt][jb][2]) | ((uint32_t)f32_to_bf16(acc[tt][jb][3]) << 16);
-                *(uint2*)(dst + 4 * jb) = pk;
+                pk.x = pack2_bf16(acc[tt][Cfg::JB - 1][0], acc[tt][Cfg::JB - 1][1]);
+                pk.y = pack2_bf16(acc[tt][Cfg::JB - 1][2], acc[tt][Cfg::JB - 1][3]);
+                *(uint2*)(blk + (4 * Cfg::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1)) = pk;
             }
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// Row copy / gather (Values follow the same token list as the Keys): 16 threads
-// per 128-channel row, 16-byte pieces.
+// Values -> fragment-major V cache: one block per 32-token block, transposed
+// through LDS; rows past the sequence end inside the last block are zero-filled.
 template <typename T>
-__global__ __launch_bounds__(256) void row_copy(RowsDev rows, int Hkv, int cap, T* __restrict__ dst)
+struct alignas(16) Oct { T v[8]; };
+
+template <typename T>
+__global__ __launch_bounds__(256) void v_retile(RowsDev rows, int Hkv, int cap, T* __restrict__ dst)
 {
     const int h = blockIdx.y, b = blockIdx.z, u = b * Hkv + h;
+    const int tid = threadIdx.x;
     const int n_b = min(rows_count(rows, b), cap);
-    const int t = blockIdx.x * 16 + (threadIdx.x >> 4);
-    if (t >= n_b) return;
-    constexpr int PIECES = (int)(D * sizeof(T) / 16 / 16);   // 16-byte pieces per thread
-    const uint4* s = (const uint4*)((const T*)rows.data + rows_offset(rows, b, h, t));
-    uint4* d = (uint4*)(dst + ((size_t)u * cap + t) * D);
-    const int c = threadIdx.x & 15;
+    const int t0 = blockIdx.x * 32;
+    if (t0 >= n_b) return;
+    __shared__ Oct<T> tile[32][17];              // 16 octets per row + 1 pad
+    const T* base = (const T*)rows.data;
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) d[c + 16 * p] = s[c + 16 * p];
+    for (int k = 0; k < 2; ++k) {
+        int p = tid + 256 * k, row = p >> 4, oc = p & 15;
+        Oct<T> x;
+        if (t0 + row < n_b) x = *(const Oct<T>*)(base + rows_offset(rows, b, h, t0 + row) + oc * 8);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x.v[e] = (T)0;
+        }
+        tile[row][oc] = x;
+    }
+    __syncthreads();
+    T* Vu = dst + (size_t)u * cap * D + (size_t)blockIdx.x * 4096;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        int o = tid + 256 * k;                   // piece index: [cb][g][n]
+        int cb = o >> 6, g = (o >> 4) & 3, n = o & 15;
+        int c = 16 * cb + n;
+        Oct<T> x;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            int tl = jj < 4 ? 4 * g + jj : 16 + 4 * g + (jj - 4);
+            x.v[jj] = tile[tl][c >> 3].v[c & 7];
+        }
+        *(Oct<T>*)(Vu + (size_t)o * 8) = x;
+    }
 }
 
 // ---------------------------------------------------------------------------
-// Append: block (h, b), 128 threads.  k~_j = sum_c k_new[c] R_r[c][j].
+// Append: block (h, b), 128 threads.  k~_j = sum_c k_new[c] R_r[c][j].  The block
+// that finishes last for a batch item bumps its length (all blocks of the item
+// read the old length before taking a ticket).
 template <typename T>
 __global__ __launch_bounds__(128) void append_rows(int Hkv, int cap, int r, const T* __restrict__ k_new,
                                                    const T* __restrict__ v_new, const float* __restrict__ Rr,
                                                    T* __restrict__ Kp, T* __restrict__ Vc,
-                                                   const int32_t* __restrict__ seq_len)
+                                                   int32_t* __restrict__ seq_len, int32_t* __restrict__ tickets)
 {
     const int h = blockIdx.x, b = blockIdx.y, u = b * Hkv + h;
     const int tid = threadIdx.x;
     const int len = seq_len[b];
-    if (len < 0 || len >= cap) return;
+    const bool ok = len >= 0 && len < cap;
     __shared__ float kn[D];
-    kn[tid] = ld_elem(k_new + (size_t)u * D + tid);
-    __syncthreads();
-    if (tid < r) {
-        const float* Ru = Rr + (size_t)u * D * r;
-        float a = 0.f;
-        for (int c = 0; c < D; ++c) a = fmaf(kn[c], Ru[c * r + tid], a);
-        st_elem(Kp + ((size_t)u * cap + len) * r + tid, a);
+    if (ok) {
+        const int rp = keep_padded(r);
+        kn[tid] = ld_elem(k_new + (size_t)u * D + tid);
+        __syncthreads();
+        if (tid < r) {
+            const float* Ru = Rr + (size_t)u * D * r;
+            float a = 0.f;
+            for (int c = 0; c < D; ++c) a = fmaf(kn[c], Ru[c * r + tid], a);
+            st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp), a);
+        }
+        Vc[(size_t)u * cap * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
     }
-    Vc[((size_t)u * cap + len) * D + tid] = v_new[(size_t)u * D + tid];
+    __syncthreads();
+    if (tid == 0) {
+        int old = atomicAdd(&tickets[b], 1);
+        if (old == Hkv - 1) {
+            tickets[b] = 0;
+            if (ok) seq_len[b] = len + 1;
+        }
+    }
 }
 
-// runs after append_rows on the same stream: every head has read the old length
-__global__ void bump_lengths(int B, int cap, int32_t* __restrict__ seq_len)
+// ---------------------------------------------------------------------------
+// Inverse re-tiling for inspection: caches -> row-major [B,H_kv,cap,r] / [B,H_kv,cap,d].
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_cache(int cap, int r, const T* __restrict__ Kp,
+                                                    const T* __restrict__ Vc, T* __restrict__ k_rows,
+                                                    T* __restrict__ v_rows)
 {
-    int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) {
-        int len = seq_len[b];
-        if (len >= 0 && len < cap) seq_len[b] = len + 1;
+    const int u = blockIdx.y;
+    const int t0 = blockIdx.x * 32;
+    const int rp = keep_padded(r);
+    if (k_rows) {
+        for (int idx = threadIdx.x; idx < 32 * r; idx += 256) {
+            int t = t0 + idx / r, j = idx % r;
+            if (t < cap) k_rows[((size_t)u * cap + t) * r + j] = Kp[(size_t)u * cap * rp + kidx(t, j, rp)];
+        }
+    }
+    if (v_rows) {
+        for (int idx = threadIdx.x; idx < 32 * D; idx += 256) {
+            int t = t0 + (idx >> 7), c = idx & 127;
+            if (t < cap) v_rows[((size_t)u * cap + t) * D + c] = Vc[(size_t)u * cap * D + vidx(t, c)];
+        }
     }
 }
 
@@ -234,29 +309,39 @@ hipError_t launch_compress(int dtype, bool mfma, const RowsDev& rows, int B, int
     return hipGetLastError();
 }
 
-hipError_t launch_row_copy(int dtype, const RowsDev& rows, int B, int Hkv, int cap, void* dst, hipStream_t st)
+hipError_t launch_v_retile(int dtype, const RowsDev& rows, int B, int Hkv, int cap, void* dst, hipStream_t st)
 {
-    int nblk = (rows.n_tokens + 15) / 16;
+    int nblk = (rows.n_tokens + 31) / 32;
     if (nblk < 1) nblk = 1;
     dim3 grid(nblk, Hkv, B);
-    if (dtype == 0) hipLaunchKernelGGL(row_copy<float>, grid, dim3(256), 0, st, rows, Hkv, cap, (float*)dst);
-    else hipLaunchKernelGGL(row_copy<bf16_t>, grid, dim3(256), 0, st, rows, Hkv, cap, (bf16_t*)dst);
+    if (dtype == 0) hipLaunchKernelGGL(v_retile<float>, grid, dim3(256), 0, st, rows, Hkv, cap, (float*)dst);
+    else hipLaunchKernelGGL(v_retile<bf16_t>, grid, dim3(256), 0, st, rows, Hkv, cap, (bf16_t*)dst);
     return hipGetLastError();
 }
 
 hipError_t launch_append(int dtype, int B, int Hkv, int cap, int r, const void* k_new, const void* v_new,
-                         const float* Rr, void* Kp, void* Vc, int32_t* seq_len, hipStream_t st)
+                         const float* Rr, void* Kp, void* Vc, int32_t* seq_len, int32_t* tickets, hipStream_t st)
 {
     dim3 grid(Hkv, B);
     if (dtype == 0)
         hipLaunchKernelGGL(append_rows<float>, grid, dim3(128), 0, st, Hkv, cap, r, (const float*)k_new,
-                           (const float*)v_new, Rr, (float*)Kp, (float*)Vc, seq_len);
+                           (const float*)v_new, Rr, (float*)Kp, (float*)Vc, seq_len, tickets);
     else
         hipLaunchKernelGGL(append_rows<bf16_t>, grid, dim3(128), 0, st, Hkv, cap, r, (const bf16_t*)k_new,
-                           (const bf16_t*)v_new, Rr, (bf16_t*)Kp, (bf16_t*)Vc, seq_len);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bump_lengths, dim3((B + 63) / 64), dim3(64), 0, st, B, cap, seq_len);
+                           (const bf16_t*)v_new, Rr, (bf16_t*)Kp, (bf16_t*)Vc, seq_len, tickets);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(int dtype, int U, int cap, int r, const void* Kp, const void* Vc, void* k_rows,
+                         void* v_rows, hipStream_t st)
+{
+    dim3 grid((cap + 31) / 32, U);
+    if (dtype == 0)
+        hipLaunchKernelGGL(unpack_cache<float>, grid, dim3(256), 0, st, cap, r, (const float*)Kp, (const float*)Vc,
+                           (float*)k_rows, (float*)v_rows);
+    else
+        hipLaunchKernelGGL(unpack_cache<bf16_t>, grid, dim3(256), 0, st, cap, r, (const bf16_t*)Kp,
+                           (const bf16_t*)Vc, (bf16_t*)k_rows, (bf16_t*)v_rows);
     return hipGetLastError();
 }
 

@@ -1,24 +1,30 @@
 // Decode-step attention over the rotated, channel-pruned Key cache (Alg. 2 steps
-// 1-3 and 6 of the RotateK paper, realised as the split-K + merge pair of
-// App. C): per split, q~ = q R_k and the bias q . delta_mu are computed in the
-// kernel's prologue, the packed Keys and full-width Values are streamed once
-// with an online softmax, and a partial (m, l, acc) goes to scratch; the merge
-// kernel folds the N_s partials.
+// 1-3 and 6 of the RotateK paper, realised as the split-K scheme of App. C): per
+// split, q~ = q R_k and the bias q . delta_mu are computed in the kernel's
+// prologue, the packed Keys and full-width Values are streamed once with an
+// online softmax, and a partial (m, l, acc) goes to scratch; the partials are
+// folded by the standard online-softmax merge.
 //
 // Differences from the paper's Triton design, made for CDNA4:
 //   - one work-group per (batch item, KV head, split) serves all G = H_q/H_kv
 //     query heads of the group, so the K/V stream is read once per KV head;
 //   - scores and P.V run on v_mfma_f32_16x16x32_bf16 with the G heads padded to
-//     16 MFMA columns; K~ rows are loaded from HBM directly in MFMA operand
-//     layout; V tiles are staged through a wave-private LDS buffer (no
-//     work-group barrier in the streaming loop);
+//     16 MFMA columns; both caches are stored fragment-major (rk_device.hpp), so
+//     every operand is one fully coalesced 16-byte-per-lane load from HBM and
+//     nothing passes through LDS in the streaming loop;
 //   - q~ and P are fed as bf16 head + remainder pairs so that the fp32 rotation
-//     and the softmax weights keep ~2^-17 relative accuracy.
+//     and the softmax weights keep ~2^-17 relative accuracy;
+//   - the split-K partials are folded by a second, tiny kernel as in the paper.
+//     (Folding them in the split kernel itself -- last work-group done -- was
+//     measured and rejected: on this multi-XCD part partials must then cross L2s
+//     as device-scope write-through stores, which cost more than a launch.)
 #include "rk_kernels.hpp"
 
 namespace rk {
 
 constexpr float NEG_INF = -__builtin_huge_valf();
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---------------------------------------------------------------------------
 // Plain kernel: one block of 128 threads per (split, query head, batch item).
@@ -56,16 +62,16 @@ __global__ __launch_bounds__(128) void decode_split_generic(
     __syncthreads();
 
     float m = NEG_INF, l = 0.f, acc = 0.f;
-    const T* Ku = Kp + (size_t)u * cap * r;
+    const int rp = keep_padded(r);
+    const T* Ku = Kp + (size_t)u * cap * rp;
     const T* Vu = Vc + (size_t)u * cap * D;
     for (int base = t0; base < t1; base += 128) {
         const int tok = base + tid;
         const bool valid = tok < t1;
         float s = NEG_INF;
         if (valid) {
-            const T* row = Ku + (size_t)tok * r;
             float a = 0.f;
-            for (int j = 0; j < r; ++j) a = fmaf(qt[j], ld_elem(row + j), a);
+            for (int j = 0; j < r; ++j) a = fmaf(qt[j], ld_elem(Ku + kidx(tok, j, rp)), a);
             s = a + bias;
         }
         float mt = wave_max(s);
@@ -82,7 +88,7 @@ __global__ __launch_bounds__(128) void decode_split_generic(
         l = l * alpha + (red[2] + red[3]);
         acc *= alpha;
         const int nv = min(128, t1 - base);
-        for (int t = 0; t < nv; ++t) acc = fmaf(ps[t], ld_elem(Vu + (size_t)(base + t) * D + tid), acc);
+        for (int t = 0; t < nv; ++t) acc = fmaf(ps[t], ld_elem(Vu + vidx(base + t, tid)), acc);
         m = m_new;
         __syncthreads();
     }
@@ -90,9 +96,9 @@ __global__ __launch_bounds__(128) void decode_split_generic(
     ws_acc[pidx * D + tid] = acc;
 }
 
-// ---------------------------------------------------------------------------
 // Merge of the N_s partials (App. C phase 2, merge part): out = sum_i acc_i w_i / sum_i l_i w_i,
-// w_i = 2^(m_i - M).  An all-empty row (M = -inf) gives zeros.
+// w_i = 2^(m_i - M).  An all-empty row (M = -inf) gives zeros.  One block per (b, h_q),
+// thread = channel; the loads of the S partials are independent and issued together.
 template <typename T>
 __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws_m, const float* __restrict__ ws_l,
                                                     const float* __restrict__ ws_acc, int S, T* __restrict__ out)
@@ -101,16 +107,26 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
     const int tid = threadIdx.x;
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
+    const float* a = ws_acc + row * S * D + tid;
     float M = NEG_INF;
     for (int i = 0; i < S; ++i) M = fmaxf(M, m[i]);
     float o = 0.f;
     if (M > NEG_INF) {
         float den = 0.f, num = 0.f;
-        for (int i = 0; i < S; ++i) {
-            float mi = m[i];
-            float w = (mi > NEG_INF) ? exp2f(mi - M) : 0.f;
+        int i = 0;
+        for (; i + 8 <= S; i += 8) {
+            float av[8], wv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) av[k] = a[(size_t)(i + k) * D];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) wv[k] = exp2f(m[i + k] - M);       // 2^(-inf) = 0 for empty splits
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { den = fmaf(l[i + k], wv[k], den); num = fmaf(av[k], wv[k], num); }
+        }
+        for (; i < S; ++i) {
+            float w = exp2f(m[i] - M);
             den = fmaf(l[i], w, den);
-            num = fmaf(ws_acc[(row * S + i) * D + tid], w, num);
+            num = fmaf(a[(size_t)i * D], w, num);
         }
         o = num / den;
     }
@@ -120,43 +136,121 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
 // ---------------------------------------------------------------------------
 // MFMA split-K kernel (bf16 cache, r a multiple of 16).  256 threads = 4 waves;
 // grid (split, H_kv * head groups of 16, B).  Each wave walks its own 32-token
-// tiles (tile index = wave, wave + 4, ...) with a private online-softmax state;
-// the four states are merged through LDS at the end.
+// tiles (tile index = wave, wave + 4, ...) with a private online-softmax state and
+// two tiles of loads in flight; the four states are merged through LDS at the end.
 //
 // Lane (g = lane / 16, n = lane % 16) register layouts:
-//   S^T = K~ Q~^T  : A = K~ rows (token n of a 16-token block, channels
-//                    32 i + 8 g ..+7: one 16-byte HBM load), B = q~ of head n;
+//   S^T = K~ Q~^T  : A = K~ fragment (token n of a 16-token block, channels
+//                    32 i + 8 g ..+7), B = q~ of head n;
 //                    result s[tb][ii] = score(token 16 tb + 4 g + ii, head n).
-//   O = P V        : A = P as produced (head n, k-slots (g, jj) <-> tokens
-//                    4 g + jj and 16 + 4 g + jj - 4), B = V[token(g, jj)][16 cb + n]
-//                    read back from LDS; result O[cb][ii] = out(head 4 g + ii,
-//                    channel 16 cb + n).
-constexpr int DEC_VROW = 272;               // bytes per staged V row (256 + 16 pad)
-constexpr int DEC_VTILE = 32 * DEC_VROW;    // 8704 B per wave, also holds 16x128 fp32 at the end
-
-// One 32-token tile: K~ rows in MFMA A-operand layout (lane (g, n): token n of each
-// 16-token block, channels 32 i + 8 g ..+7, plus 4 channels of a k = 16 tail) and
-// 8 KB of V as 16-byte pieces (row 4 u8 + g, piece n).  Rows past the split's end
-// are clamped to its last valid row; their scores are masked later.
+//   O = P V        : A = P as produced (head n, k-slot (g, jj) <-> token
+//                    4 g + jj (jj < 4) or 16 + 4 g + jj - 4), B = V fragment
+//                    (channel 16 cb + n, the same 8 tokens); result
+//                    O[cb][ii] = out(head 4 g + ii, channel 16 cb + n).
 template <int R>
-__device__ __forceinline__ void load_tile(const bf16_t* __restrict__ Ku, const bf16_t* __restrict__ Vu, int tb0,
-                                          int t1, int g, int n, bf16x8 (&kf)[2][(R / 32) > 0 ? (R / 32) : 1],
-                                          s16x4 (&kt)[2], uint4 (&vf)[8])
+struct DecTile {
+    static constexpr int NF = R / 32;
+    static constexpr int NFA = NF > 0 ? NF : 1;
+    static constexpr bool TAIL = (R % 32) != 0;
+    bf16x8 kf[2][NFA];
+    s16x4 kt[2];
+    bf16x8 vf[8];
+};
+
+template <int R>
+__device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restrict__ Ku,
+                                          const bf16_t* __restrict__ Vu, int tok0, int lane)
 {
-    constexpr int NF = R / 32;
-    constexpr bool TAIL = (R % 32) != 0;
+    const bf16_t* kb = Ku + (size_t)(tok0 >> 4) * (16 * R) + lane * 8;
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-        int tok = min(tb0 + 16 * tb + n, t1 - 1);
-        const bf16_t* kr = Ku + (size_t)tok * R;
 #pragma unroll
-        for (int i = 0; i < NF; ++i) kf[tb][i] = *(const bf16x8*)(kr + 32 * i + 8 * g);
-        if (TAIL) kt[tb] = *(const s16x4*)(kr + 32 * NF + 4 * g);
+        for (int i = 0; i < DecTile<R>::NF; ++i) T.kf[tb][i] = *(const bf16x8*)(kb + tb * 16 * R + i * 512);
+        if (DecTile<R>::TAIL) {
+            const int g = lane >> 4, n = lane & 15;
+            T.kt[tb] = *(const s16x4*)(Ku + (size_t)((tok0 >> 4) + tb) * (16 * R) +
+                                       (4 * DecTile<R>::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1));
+        }
     }
+    const bf16_t* vb = Vu + (size_t)(tok0 >> 5) * 4096 + lane * 8;
 #pragma unroll
-    for (int u8 = 0; u8 < 8; ++u8) {
-        int tok = min(tb0 + 4 * u8 + g, t1 - 1);
-        vf[u8] = *(const uint4*)(Vu + (size_t)tok * D + 8 * n);
+    for (int cb = 0; cb < 8; ++cb) T.vf[cb] = *(const bf16x8*)(vb + cb * 512);
+}
+
+template <int R>
+struct DecState {
+    float m_run, l_run;
+    f32x4 O[8];
+};
+
+template <int R>
+__device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, const bf16x8 (&qh)[DecTile<R>::NFA],
+                                             const bf16x8 (&ql)[DecTile<R>::NFA], s16x4 qth, s16x4 qtl, int tok0,
+                                             int t1, int g)
+{
+    f32x4 s[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        s[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < DecTile<R>::NF; ++i) {
+            s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.kf[tb][i], qh[i], s[tb], 0, 0, 0);
+            s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.kf[tb][i], ql[i], s[tb], 0, 0, 0);
+        }
+        if (DecTile<R>::TAIL) {
+            s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qth, s[tb], 0, 0, 0);
+            s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qtl, s[tb], 0, 0, 0);
+        }
+    }
+    if (tok0 + 32 > t1) {
+        // last, partial tile of the split: rows past the end may hold anything (even NaN
+        // patterns), so mask their scores and zero their Value slots
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii)
+                if (tok0 + 16 * tb + 4 * g + ii >= t1) s[tb][ii] = NEG_INF;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                int tl = jj < 4 ? 4 * g + jj : 16 + 4 * g + (jj - 4);
+                if (tok0 + tl >= t1) T.vf[cb][jj] = (__bf16)0.f;
+            }
+    }
+    float mt = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mt = fmaxf(mt, __shfl_xor(mt, 16));
+    mt = fmaxf(mt, __shfl_xor(mt, 32));
+    const float m_new = fmaxf(st.m_run, mt);
+    const float alpha = fast_exp2(st.m_run - m_new);
+    float psum = 0.f;
+    bf16x8 ph, pl;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            float p = fast_exp2(s[tb][ii] - m_new);
+            psum += p;
+            __bf16 hi, lo;
+            split_bf16(p, hi, lo);
+            ph[4 * tb + ii] = hi;
+            pl[4 * tb + ii] = lo;
+        }
+    st.l_run = fmaf(st.l_run, alpha, psum);
+    if (__any(m_new > st.m_run)) {
+        // alpha lives in lanes (., n = head); the accumulators need alpha of heads 4 g + ii
+        f32x4 a4;
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) a4[ii] = __shfl(alpha, 4 * g + ii);
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) st.O[cb] *= a4;
+    }
+    st.m_run = m_new;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        st.O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, T.vf[cb], st.O[cb], 0, 0, 0);
+        st.O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, T.vf[cb], st.O[cb], 0, 0, 0);
     }
 }
 
@@ -165,17 +259,17 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vc,
     const float* __restrict__ Rr, const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq,
     int Hkv, int cap, int tps, float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l,
-    float* __restrict__ ws_acc, int S)
+    float* __restrict__ ws_acc, int S, bf16_t* __restrict__ out)
 {
-    constexpr int NF = R / 32;                 // k = 32 steps over the kept channels
-    constexpr bool TAIL = (R % 32) != 0;       // plus one k = 16 step
-    constexpr int NFA = NF > 0 ? NF : 1;
+    typedef DecTile<R> Tile;
+    constexpr int NF = Tile::NF, NFA = Tile::NFA;
+    constexpr bool TAIL = Tile::TAIL;
 
-    __shared__ __attribute__((aligned(16))) unsigned char vt[4][DEC_VTILE];
+    // big: q~ partial sums [4][16][R] in the prologue, the four waves' O [4][16][128] at the end
+    __shared__ __attribute__((aligned(16))) float big[4 * 16 * D];
     __shared__ float qs[16][D];
     __shared__ float qt[16][R];
     __shared__ float sbias[16];
-    __shared__ __attribute__((aligned(16))) float salpha[4][16];
     __shared__ float sm_m[4][16], sm_l[4][16];
 
     const int G = Hq / Hkv;
@@ -190,194 +284,153 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 
     const int L = min(max(seq_len[b], 0), cap);
     const int t0 = split * tps, t1 = min(t0 + tps, L);
-    if (t0 >= t1) {
-        for (int idx = tid; idx < Gc * D; idx += 256) {
-            int hh = idx >> 7, c = idx & 127;
-            size_t pidx = ((size_t)b * Hq + h0 + hh) * S + split;
-            ws_acc[pidx * D + c] = 0.f;
-            if (c == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
-        }
-        return;
-    }
+    const bool empty = t0 >= t1;
 
-    const bf16_t* Ku = Kp + (size_t)u * cap * R;
-    const bf16_t* Vu = Vc + (size_t)u * cap * D;
-    const int ntiles = (t1 - t0 + 31) >> 5;
+    if (!empty) {
+        const bf16_t* Ku = Kp + (size_t)u * cap * R;
+        const bf16_t* Vu = Vc + (size_t)u * cap * D;
+        const int ntiles = (t1 - t0 + 31) >> 5;
 
-    // ---- tile loads (issued before the prologue so HBM latency overlaps it) ----
-    bf16x8 kf[2][NFA];
-    s16x4 kt[2];
-    uint4 vf[8];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        kt[tb] = (s16x4){0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < NFA; ++i) kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-    }
-#pragma unroll
-    for (int u8 = 0; u8 < 8; ++u8) vf[u8] = make_uint4(0, 0, 0, 0);
-    if (wave < ntiles) load_tile<R>(Ku, Vu, t0 + wave * 32, t1, g, n, kf, kt, vf);
-
-    // ---- prologue: q~ = q R_r (scaled into the log2 domain), bias ---------------
-    for (int idx = tid; idx < 16 * D; idx += 256) {
-        int hh = idx >> 7, c = idx & 127;
-        qs[hh][c] = hh < Gc ? bf16_to_f32(q[((size_t)b * Hq + h0 + hh) * D + c]) : 0.f;
-    }
-    __syncthreads();
-    {
-        const float* Ru = Rr + (size_t)u * D * R;
-        for (int idx = tid; idx < 16 * R; idx += 256) {
-            int hh = idx / R, j = idx - hh * R;
-            float a = 0.f;
-            if (hh < Gc) {
-#pragma unroll 8
-                for (int c = 0; c < D; ++c) a = fmaf(qs[hh][c], Ru[c * R + j], a);
-            }
-            qt[hh][j] = a * scale_log2;
-        }
-        if (tid < 16) {
-            float a = 0.f;
-            if (tid < Gc && dmu) {
-                const float* dm = dmu + (size_t)u * D;
-                for (int c = 0; c < D; ++c) a = fmaf(qs[tid][c], dm[c], a);
-            }
-            sbias[tid] = a * scale_log2;
-        }
-    }
-    __syncthreads();
-
-    // B operands of the score MFMAs: q~ of head n, split into bf16 head + remainder
-    bf16x8 qh[NFA], ql[NFA];
-    s16x4 qth, qtl;
-#pragma unroll
-    for (int i = 0; i < NF; ++i) {
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            __bf16 hi, lo;
-            split_bf16(qt[n][32 * i + 8 * g + jj], hi, lo);
-            qh[i][jj] = hi;
-            ql[i][jj] = lo;
-        }
-    }
-    if (TAIL) {
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            __bf16 hi, lo;
-            split_bf16(qt[n][32 * NF + 4 * g + jj], hi, lo);
-            qth[jj] = __builtin_bit_cast(short, hi);
-            qtl[jj] = __builtin_bit_cast(short, lo);
-        }
-    }
-
-    float m_run = NEG_INF, l_run = 0.f;
-    f32x4 O[8];
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    unsigned char* vw = vt[wave];
-
-    for (int tile = wave; tile < ntiles; tile += 4) {
-        const int tb0 = t0 + tile * 32;
-        // stage this tile's V rows (row 4 u8 + g, 16-byte piece n) and free the registers
-#pragma unroll
-        for (int u8 = 0; u8 < 8; ++u8) *(uint4*)(vw + (4 * u8 + g) * DEC_VROW + 16 * n) = vf[u8];
-
-        // scores
-        f32x4 s[2];
+        // two tiles of loads go out before the prologue so HBM latency overlaps it
+        Tile TA, TB;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
-            s[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            TA.kt[tb] = (s16x4){0, 0, 0, 0};
+            TB.kt[tb] = (s16x4){0, 0, 0, 0};
 #pragma unroll
-            for (int i = 0; i < NF; ++i) {
-                s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tb][i], qh[i], s[tb], 0, 0, 0);
-                s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tb][i], ql[i], s[tb], 0, 0, 0);
-            }
-            if (TAIL) {
-                s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt[tb], qth, s[tb], 0, 0, 0);
-                s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt[tb], qtl, s[tb], 0, 0, 0);
+            for (int i = 0; i < NFA; ++i) {
+                TA.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+                TB.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
             }
         }
-        // K~ registers are consumed: prefetch the wave's next tile
-        if (tile + 4 < ntiles) load_tile<R>(Ku, Vu, tb0 + 128, t1, g, n, kf, kt, vf);
-
-        // online softmax for head n over this lane's 8 tokens
-        float mt = NEG_INF;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                int tok = tb0 + 16 * tb + 4 * g + ii;
-                float sv = tok < t1 ? s[tb][ii] : NEG_INF;
-                s[tb][ii] = sv;
-                mt = fmaxf(mt, sv);
-            }
-        mt = fmaxf(mt, __shfl_xor(mt, 16));
-        mt = fmaxf(mt, __shfl_xor(mt, 32));
-        const float m_new = fmaxf(m_run, mt);
-        const float alpha = exp2f(m_run - m_new);
-        float psum = 0.f;
-        bf16x8 ph, pl;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                float p = exp2f(s[tb][ii] - m_new);
-                psum += p;
-                __bf16 hi, lo;
-                split_bf16(p, hi, lo);
-                ph[4 * tb + ii] = hi;
-                pl[4 * tb + ii] = lo;
-            }
-        l_run = fmaf(l_run, alpha, psum);
-        if (__any(m_new > m_run)) {
-            // alpha lives in lanes (., n = head); the accumulators need alpha[4 g + ii]
-            if (g == 0) salpha[wave][n] = alpha;
-            wave_lds_fence();
-            f32x4 a4 = *(const f32x4*)&salpha[wave][4 * g];
-#pragma unroll
-            for (int cb = 0; cb < 8; ++cb) O[cb] *= a4;
-        }
-        m_run = m_new;
-        wave_lds_fence();
-
-        // O += P V
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) {
-            bf16x8 vb;
+            TA.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            TB.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        }
+        if (wave < ntiles) load_tile<R>(TA, Ku, Vu, t0 + wave * 32, lane);
+        if (wave + 4 < ntiles) load_tile<R>(TB, Ku, Vu, t0 + (wave + 4) * 32, lane);
+
+        // ---- prologue: q~ = q R_r scaled into the log2 domain, and the bias ------------
+        for (int idx = tid; idx < 16 * D; idx += 256) {
+            int hh = idx >> 7, c = idx & 127;
+            qs[hh][c] = hh < Gc ? bf16_to_f32(q[((size_t)b * Hq + h0 + hh) * D + c]) : 0.f;
+        }
+        __syncthreads();
+        {
+            // item (cq, j): partial sums over channels [32 cq, 32 cq + 32) for all heads;
+            // the 32 loads of R_r are independent, so one memory round trip covers them
+            const float* Ru = Rr + (size_t)u * D * R;
+            for (int idx = tid; idx < 4 * R; idx += 256) {
+                int cq = idx / R, j = idx - cq * R;
+                float x[32];
+#pragma unroll
+                for (int c = 0; c < 32; ++c) x[c] = Ru[(32 * cq + c) * R + j];
+                for (int hh = 0; hh < 16; ++hh) {
+                    float a = 0.f;
+                    if (hh < Gc) {
+#pragma unroll
+                        for (int c = 0; c < 32; ++c) a = fmaf(qs[hh][32 * cq + c], x[c], a);
+                    }
+                    big[(cq * 16 + hh) * R + j] = a;
+                }
+            }
+            if (tid < 16) {
+                float a = 0.f;
+                if (tid < Gc && dmu) {
+                    const float* dm = dmu + (size_t)u * D;
+                    for (int c = 0; c < D; ++c) a = fmaf(qs[tid][c], dm[c], a);
+                }
+                sbias[tid] = a * scale_log2;
+            }
+        }
+        __syncthreads();
+        for (int idx = tid; idx < 16 * R; idx += 256) {
+            int hh = idx / R, j = idx - hh * R;
+            float a = (big[(0 * 16 + hh) * R + j] + big[(1 * 16 + hh) * R + j]) +
+                      (big[(2 * 16 + hh) * R + j] + big[(3 * 16 + hh) * R + j]);
+            qt[hh][j] = a * scale_log2;
+        }
+        __syncthreads();
+
+        // B operands of the score MFMAs: q~ of head n, split into bf16 head + remainder
+        bf16x8 qh[NFA], ql[NFA];
+        s16x4 qth = (s16x4){0, 0, 0, 0}, qtl = (s16x4){0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < NFA; ++i) {
+            qh[i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            ql[i] = qh[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
-                int tl = jj < 4 ? 4 * g + jj : 16 + 4 * g + (jj - 4);
-                vb[jj] = *(const __bf16*)(vw + tl * DEC_VROW + 2 * (16 * cb + n));
+                __bf16 hi, lo;
+                split_bf16(qt[n][32 * i + 8 * g + jj], hi, lo);
+                qh[i][jj] = hi;
+                ql[i][jj] = lo;
             }
-            O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, vb, O[cb], 0, 0, 0);
-            O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, vb, O[cb], 0, 0, 0);
         }
-        wave_lds_fence();
-    }
+        if (TAIL) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                __bf16 hi, lo;
+                split_bf16(qt[n][32 * NF + 4 * g + jj], hi, lo);
+                qth[jj] = __builtin_bit_cast(short, hi);
+                qtl[jj] = __builtin_bit_cast(short, lo);
+            }
+        }
 
-    // ---- merge the four waves' states, write the split's partial -----------------
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    float* ow = (float*)vw;                   // [16 heads][128 channels]
+        DecState<R> st;
+        st.m_run = NEG_INF;
+        st.l_run = 0.f;
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
+        for (int cb = 0; cb < 8; ++cb) st.O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+        for (int tile = wave; tile < ntiles; tile += 8) {
+            compute_tile<R>(TA, st, qh, ql, qth, qtl, t0 + tile * 32, t1, g);
+            if (tile + 8 < ntiles) load_tile<R>(TA, Ku, Vu, t0 + (tile + 8) * 32, lane);
+            if (tile + 4 < ntiles) {
+                compute_tile<R>(TB, st, qh, ql, qth, qtl, t0 + (tile + 4) * 32, t1, g);
+                if (tile + 12 < ntiles) load_tile<R>(TB, Ku, Vu, t0 + (tile + 12) * 32, lane);
+            }
+        }
+
+        // ---- merge the four waves' states ----------------------------------------------
+        float l_run = st.l_run;
+        l_run += __shfl_xor(l_run, 16);
+        l_run += __shfl_xor(l_run, 32);
+        float* ow = big + wave * (16 * D);        // [16 heads][128 channels]
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) ow[(4 * g + ii) * D + 16 * cb + n] = O[cb][ii];
-    if (g == 0) { sm_m[wave][n] = m_run; sm_l[wave][n] = l_run; }
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) ow[(4 * g + ii) * D + 16 * cb + n] = st.O[cb][ii];
+        if (g == 0) { sm_m[wave][n] = st.m_run; sm_l[wave][n] = l_run; }
+    }
     __syncthreads();
+
+    // ---- the split's result: straight to `out` if it is the only split, else a partial ----
     for (int idx = tid; idx < Gc * D; idx += 256) {
         int hh = idx >> 7, c = idx & 127;
-        float M = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
-        float lsum = 0.f, a = 0.f;
+        const size_t row = (size_t)b * Hq + h0 + hh;
+        float M = NEG_INF, lsum = 0.f, a = 0.f;
+        if (!empty) {
+            M = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            float mw = sm_m[w][hh];
-            float wgt = (mw > NEG_INF) ? exp2f(mw - M) : 0.f;
-            lsum = fmaf(sm_l[w][hh], wgt, lsum);
-            a = fmaf(((const float*)vt[w])[hh * D + c], wgt, a);
+            for (int w = 0; w < 4; ++w) {
+                float mw = sm_m[w][hh];
+                float wgt = (mw > NEG_INF) ? fast_exp2(mw - M) : 0.f;
+                lsum = fmaf(sm_l[w][hh], wgt, lsum);
+                a = fmaf(big[(w * 16 + hh) * D + c], wgt, a);
+            }
         }
-        size_t pidx = ((size_t)b * Hq + h0 + hh) * S + split;
-        ws_acc[pidx * D + c] = a;
-        if (c == 0) { ws_m[pidx] = M + sbias[hh]; ws_l[pidx] = lsum; }
+        if (S == 1) {
+            out[row * D + c] = f32_to_bf16(empty ? 0.f : a / lsum);
+        } else {
+            const size_t pidx = row * S + split;
+            ws_acc[pidx * D + c] = a;                   // an empty split stores zeros with m = -inf
+            if (c == 0) { ws_m[pidx] = empty ? NEG_INF : M + sbias[hh]; ws_l[pidx] = lsum; }
+        }
     }
 }
 
@@ -387,10 +440,10 @@ bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r % 16 == 0 
 template <int R>
 static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, const bf16_t* Kp, const bf16_t* Vc,
                                  const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv,
-                                 int cap, int tps, float sl2, float* m, float* l, float* acc, int S)
+                                 int cap, int tps, float sl2, float* m, float* l, float* acc, int S, bf16_t* out)
 {
     hipLaunchKernelGGL(decode_split_mfma<R>, grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv, cap,
-                       tps, sl2, m, l, acc, S);
+                       tps, sl2, m, l, acc, S, out);
 }
 
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
@@ -409,24 +462,27 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
         launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tps, sl2, ws_m, ws_l, \
-                                 ws_acc, S);                                                               \
+                                 ws_acc, S, (bf16_t*)out);                                                 \
         break;
         switch (r) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
             default: return hipErrorInvalidValue;
         }
 #undef RK_CASE
-    } else {
-        dim3 grid(S, Hq, B);
-        if (dtype == 0)
-            hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q,
-                               (const float*)Kp, (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
-                               ws_m, ws_l, ws_acc, S);
-        else
-            hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
-                               (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
-                               ws_m, ws_l, ws_acc, S);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess || S == 1) return e0;       // a single split writes `out` itself
+        hipLaunchKernelGGL(decode_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
+                           (bf16_t*)out);
+        return hipGetLastError();
     }
+    dim3 grid(S, Hq, B);
+    if (dtype == 0)
+        hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q, (const float*)Kp,
+                           (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2, ws_m, ws_l, ws_acc, S);
+    else
+        hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
+                           (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
+                           ws_m, ws_l, ws_acc, S);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dtype == 0)

@@ -64,6 +64,32 @@ __device__ __forceinline__ int64_t rows_offset(const RowsDev& r, int b, int h, i
     return (int64_t)b * r.sb + (int64_t)h * r.sh + row * r.st;
 }
 
+// ---------------------------------------------------------------------------
+// Cache layouts (element indices within one (batch item, KV head) slab).  Both
+// caches are tiled so that a wave's MFMA operand fragment is ONE contiguous
+// 1 KB piece of HBM (lane l reads bytes [16 l, 16 l + 16)):
+//
+//  packed Keys K~: blocks of 16 tokens; inside a block channel octets are the
+//    slow axis:   [t / 16][c / 8][t % 16][c % 8]        (r padded to a multiple of 8)
+//    A 16x16x32 MFMA A-fragment of k-step i is octets 4i..4i+3 of a block:
+//    lane (g, n) holds token n, channels 32 i + 8 g ..+7.
+//
+//  Values V: blocks of 32 tokens:  [t / 32][c / 16][g][c % 16][jj]  where the
+//    token's position in its block, tl = t % 32, maps to k-slot (g, jj) with
+//    g = (tl % 16) / 4,  jj = 4 (tl / 16) + tl % 4.  This is exactly how the score
+//    MFMA hands the softmax weights of 32 tokens to lane group g, so P feeds the
+//    P.V MFMA as produced and lane (g, n) reads V's B-fragment for channel block
+//    cb as one 16-byte piece.
+__host__ __device__ __forceinline__ int keep_padded(int r) { return (r + 7) & ~7; }
+__host__ __device__ __forceinline__ size_t kidx(int t, int c, int rp) {
+    return (size_t)(t >> 4) * (16 * (size_t)rp) + (size_t)(c >> 3) * 128 + (size_t)(t & 15) * 8 + (c & 7);
+}
+__host__ __device__ __forceinline__ size_t vidx(int t, int c) {
+    int tl = t & 31;
+    int g = (tl & 15) >> 2, jj = ((tl >> 4) << 2) | (tl & 3);
+    return (size_t)(t >> 5) * 4096 + (size_t)(c >> 4) * 512 + (size_t)g * 128 + (size_t)(c & 15) * 8 + jj;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n
 // Columns never move: eigenvalue c is the final A[c][c] and its vector is V[:, c].
 constexpr int EIG_THREADS = 1024;
 constexpr int EIG_MAX_SWEEPS = 20;
-constexpr size_t EIG_LDS_BYTES = (size_t)(2 * D * D + 2 * 64 + 2 * D + 64) * sizeof(float) + D * sizeof(int);
+constexpr size_t EIG_LDS_BYTES = (size_t)(2 * D * D + 3 * 64 + 2 * D + 64) * sizeof(float) + D * sizeof(int);
 
 __device__ __forceinline__ void rr_pair(int round, int k, int& p, int& q) {
     // circle method on n-1 = 127 rotating players, player 127 fixed
@@ -135,9 +135,10 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
     extern __shared__ float sm[];
     float* A = sm;                        // [128][128]
     float* V = A + D * D;                 // [128][128]
-    float* rc = V + D * D;                // [64] cos
-    float* rs = rc + 64;                  // [64] sin
-    float* slam = rs + 64;                // [128]
+    float* rs = V + D * D;                // [64] sin
+    float* rtau = rs + 64;                // [64] sin / (1 + cos)
+    float* rt = rtau + 64;                // [64] tan
+    float* slam = rt + 64;                // [128]
     float* sw = slam + D;                 // [128] scratch (R_r^T mu)
     float* red = sw + D;                  // [64] reduction scratch
     int* skeep = (int*)(red + 64);        // [128]
@@ -188,35 +189,42 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
                 int p, q;
                 rr_pair(round, tid, p, q);
                 float app = A[p * D + p], aqq = A[q * D + q], apq = A[p * D + q];
-                float c = 1.f, s = 0.f;
+                // Rotations are applied as x' = x - s (y + tau x), y' = y + s (x - tau y) with
+                // tau = s / (1 + c): 1 - c is then carried to relative precision, so small
+                // angles (c rounding to 1) do not inflate the column norms of V.
+                float s = 0.f, tau = 0.f, t = 0.f;
                 if (fabsf(apq) > thr_skip) {
-                    float tau = (aqq - app) / (2.f * apq);
-                    float t = copysignf(1.f, tau) / (fabsf(tau) + sqrtf(fmaf(tau, tau, 1.f)));
-                    c = 1.f / sqrtf(fmaf(t, t, 1.f));
+                    float th = (aqq - app) / (2.f * apq);
+                    t = copysignf(1.f, th) / (fabsf(th) + sqrtf(fmaf(th, th, 1.f)));
+                    float c = 1.f / sqrtf(fmaf(t, t, 1.f));
                     s = t * c;
+                    tau = s / (1.f + c);
                 }
-                rc[tid] = c;
                 rs[tid] = s;
+                rtau[tid] = tau;
+                rt[tid] = t;
             }
             __syncthreads();
             int p2, q2;
             rr_pair(round, lane, p2, q2);
-            const float c2 = rc[lane], s2 = rs[lane];
+            const float s2 = rs[lane], tau2 = rtau[lane];
             // A <- J^T A J : 64 x 64 blocks, wave handles pair-rows k = wave + 16 it
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 int k = wave + 16 * it;
                 int p, q;
                 rr_pair(round, k, p, q);
-                float c1 = rc[k], s1 = rs[k];
+                float s1 = rs[k], tau1 = rtau[k];
                 float a00 = A[p * D + p2], a01 = A[p * D + q2];
                 float a10 = A[q * D + p2], a11 = A[q * D + q2];
-                float b00 = c1 * a00 - s1 * a10, b01 = c1 * a01 - s1 * a11;
-                float b10 = s1 * a00 + c1 * a10, b11 = s1 * a01 + c1 * a11;
-                float e00 = c2 * b00 - s2 * b01, e01 = s2 * b00 + c2 * b01;
-                float e10 = c2 * b10 - s2 * b11, e11 = s2 * b10 + c2 * b11;
+                // rows p, q : J^T from the left
+                float b00 = a00 - s1 * (a10 + tau1 * a00), b01 = a01 - s1 * (a11 + tau1 * a01);
+                float b10 = a10 + s1 * (a00 - tau1 * a10), b11 = a11 + s1 * (a01 - tau1 * a11);
+                // columns p', q' : J from the right
+                float e00 = b00 - s2 * (b01 + tau2 * b00), e01 = b01 + s2 * (b00 - tau2 * b01);
+                float e10 = b10 - s2 * (b11 + tau2 * b10), e11 = b11 + s2 * (b10 - tau2 * b11);
                 if (k == lane) {           // the pair's own block: annihilated exactly
-                    float t = s1 / c1;
+                    float t = rt[k];
                     e00 = a00 - t * a01;
                     e11 = a11 + t * a01;
                     e01 = 0.f;
@@ -230,8 +238,8 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
             for (int it = 0; it < 8; ++it) {
                 int i = wave + 16 * it;
                 float v0 = V[i * D + p2], v1 = V[i * D + q2];
-                V[i * D + p2] = c2 * v0 - s2 * v1;
-                V[i * D + q2] = s2 * v0 + c2 * v1;
+                V[i * D + p2] = v0 - s2 * (v1 + tau2 * v0);
+                V[i * D + q2] = v1 + s2 * (v0 - tau2 * v1);
             }
             __syncthreads();
         }

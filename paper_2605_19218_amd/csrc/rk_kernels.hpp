@@ -22,9 +22,12 @@ hipError_t launch_gather_rotation(int U, int r, const float* R, const int32_t* k
 // ---- rk_compress.hip -------------------------------------------------------
 hipError_t launch_compress(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int cap, int r,
                            const float* Rr, void* Kp, int32_t* seq_len_out, hipStream_t st);
-hipError_t launch_row_copy(int dtype, const RowsDev& rows, int B, int Hkv, int cap, void* dst, hipStream_t st);
+hipError_t launch_v_retile(int dtype, const RowsDev& rows, int B, int Hkv, int cap, void* dst, hipStream_t st);
+// tickets: B zero-initialised ints, left at zero on completion
 hipError_t launch_append(int dtype, int B, int Hkv, int cap, int r, const void* k_new, const void* v_new,
-                         const float* Rr, void* Kp, void* Vc, int32_t* seq_len, hipStream_t st);
+                         const float* Rr, void* Kp, void* Vc, int32_t* seq_len, int32_t* tickets, hipStream_t st);
+hipError_t launch_unpack(int dtype, int U, int cap, int r, const void* Kp, const void* Vc, void* k_rows,
+                         void* v_rows, hipStream_t st);
 
 // ---- rk_decode.hip ---------------------------------------------------------
 // Partials: m [B,Hq,S], l [B,Hq,S], acc [B,Hq,S,d]; m is in the log2 domain.

@@ -47,6 +47,7 @@ class Pipeline:
     """Device buffers of one layer + calls through the binding."""
 
     def __init__(self, ctx, B, Hq, Hkv, r, dtype, capacity):
+        capacity = (capacity + 31) // 32 * 32           # the caches are tiled in 32-token blocks
         self.ctx, self.B, self.Hq, self.Hkv, self.r, self.dtype, self.cap = ctx, B, Hq, Hkv, r, dtype, capacity
         U = B * Hkv
         f32 = dict(device=DEV, dtype=torch.float32)
@@ -59,15 +60,25 @@ class Pipeline:
         self.dmu = torch.zeros(B, Hkv, D, **f32)
         self.cov = torch.zeros(B, Hkv, D, D, **f32)
         td = torch_dtype(dtype)
-        self.Kp = torch.zeros(B, Hkv, capacity, r, device=DEV, dtype=td)
-        self.Vc = torch.zeros(B, Hkv, capacity, D, device=DEV, dtype=td)
         self.seq_len = torch.zeros(B, device=DEV, dtype=torch.int32)
-        self.out = torch.zeros(B, Hq, D, device=DEV, dtype=td)
         self.max_seq_len = 0
+        kb, vb = rk.rk_cache_bytes(self.layout())
+        self.Kp = torch.zeros(kb, device=DEV, dtype=torch.uint8)     # opaque fragment-major caches
+        self.Vc = torch.zeros(vb, device=DEV, dtype=torch.uint8)
+        self.out = torch.zeros(B, Hq, D, device=DEV, dtype=td)
 
     def layout(self):
         return rk.Layout(self.B, self.Hq, self.Hkv, self.r, rk_dtype(self.dtype), self.cap, self.max_seq_len,
                          seq_len=self.seq_len)
+
+    def unpacked(self):
+        """(K~ [B,Hkv,cap,r], V [B,Hkv,cap,d]) as fp64 numpy, via rk_unpack_cache."""
+        td = torch_dtype(self.dtype)
+        k_rows = torch.zeros(self.B, self.Hkv, self.cap, self.r, device=DEV, dtype=td)
+        v_rows = torch.zeros(self.B, self.Hkv, self.cap, D, device=DEV, dtype=td)
+        rk.rk_unpack_cache(self.ctx, self.layout(), self.Kp, self.Vc, k_rows, v_rows)
+        torch.cuda.synchronize()
+        return to_host(k_rows), to_host(v_rows)
 
     def rows(self, t, n_tokens, n_dev=None, tok_idx=None, tok_off=None):
         return rk.Rows(t, n_tokens, n_tokens_dev=n_dev, tok_idx=tok_idx, tok_off=tok_off)

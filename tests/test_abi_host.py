@@ -62,6 +62,7 @@ def test_layout_validation():
     assert rk.rk_validate_layout(layout(keep=0)) == rk.RK_ERR_INVALID_ARG
     assert rk.rk_validate_layout(layout(keep=129)) == rk.RK_ERR_INVALID_ARG
     assert rk.rk_validate_layout(layout(capacity=0)) == rk.RK_ERR_INVALID_ARG
+    assert rk.rk_validate_layout(layout(capacity=1000)) == rk.RK_ERR_INVALID_ARG      # not a multiple of 32
     assert rk.rk_validate_layout(layout(batch=0)) == rk.RK_ERR_INVALID_ARG
     assert rk.lib().rk_validate_layout(None) == rk.RK_ERR_INVALID_ARG
 
@@ -118,6 +119,12 @@ def test_compress_append_validation(ctx):
     assert status_of(rk.rk_append, ctx, lay, PTR, None, PTR, PTR, PTR, PTR) == rk.RK_ERR_INVALID_ARG
     assert status_of(rk.rk_gather_rotation, ctx, lay, PTR, PTR, PTR) == rk.RK_ERR_NO_DEVICE
     assert status_of(rk.rk_gather_rotation, ctx, lay, PTR, None, PTR) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_unpack_cache, ctx, lay, PTR, PTR, PTR, PTR) == rk.RK_ERR_NO_DEVICE
+    assert status_of(rk.rk_unpack_cache, ctx, lay, None, PTR, PTR, None) == rk.RK_ERR_INVALID_ARG
+    assert status_of(rk.rk_unpack_cache, ctx, lay, PTR, PTR, None, None) == rk.RK_ERR_INVALID_ARG
+    # cache sizes: keep is padded to a multiple of 8 channels
+    assert rk.rk_cache_bytes(lay) == (2 * 2 * 1024 * 64 * 2, 2 * 2 * 1024 * 128 * 2)
+    assert rk.rk_cache_bytes(layout(keep=37, dtype=rk.RK_F32))[0] == 2 * 2 * 1024 * 40 * 4
 
 
 def test_decode_plan_and_options(ctx):

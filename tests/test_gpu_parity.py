@@ -59,8 +59,7 @@ def check_packed(got, K_rows, Rr, dtype):
 
 
 def oracle_decode(p, q, lens, use_bias=True, scale=0.0):
-    Kt = to_host(p.Kp)
-    V = to_host(p.Vc)
+    Kt, V = p.unpacked()
     Rr = to_host(p.Rr)
     dmu = to_host(p.dmu) if use_bias else None
     return oracle.decode_batch(q.astype(np.float64), Kt, V, Rr, dmu, lens=np.asarray(lens, np.int32), scale=scale)
@@ -133,11 +132,17 @@ def test_eig_invariants_and_mask(ctx, with_sigma):
             assert np.array_equal(Rr[b, h], Rm[:, k_o])
             d_o = oracle.delta_mu(mu[b, h], Rr[b, h])
             assert np.abs(dmu[b, h] - d_o).max() <= TOL_F32 * max(np.abs(mu[b, h]).max(), 1e-30)
-            # top-r subspace against the oracle's independent eigensolve where the gap is large
+            # top-18 subspace (16 signal + 2 outlier directions, a 100x eigenvalue gap) against the
+            # oracle's independent fp64 eigensolve of the exact covariance.  Davis-Kahan:
+            # ||P_gpu - P_oracle||_2 <= ||E||_2 / gap, E = (C_gpu - C_exact) + solver residual.
             f = oracle.fit(data["K"][b, h], 18, sigma=None if sigma is None else sg[b, h])
             P_o = f["Rr"] @ f["Rr"].T
             top = Rm[:, np.argsort(-lm)[:18]]
-            assert np.abs(top @ top.T - P_o).max() <= 1e-4
+            gap = f["lam"][17] - f["lam"][18]
+            E = np.linalg.norm(Cq - f["Cq"], 2) + np.linalg.norm(resid, 2)
+            dist = np.linalg.norm(top @ top.T - P_o, 2)
+            assert dist <= 2.0 * E / gap + 1e-5, (dist, E / gap)
+            assert dist <= 5e-3
     # rk_gather_rotation re-derives R_r from (R, keep_idx)
     Rr2 = torch.zeros_like(p.Rr)
     rk.rk_gather_rotation(ctx, p.layout(), p.R, p.keep_idx, Rr2)
@@ -159,7 +164,7 @@ def test_compress_parity(ctx, dtype, r, generic):
         p = run_prefill(ctx, data, B, Hkv, Hkv, L, r, dtype, lengths=lengths)
     finally:
         rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
-    Kt, Rr, Vc = to_host(p.Kp), to_host(p.Rr), to_host(p.Vc)
+    (Kt, Vc), Rr = p.unpacked(), to_host(p.Rr)
     assert p.seq_len.cpu().tolist() == lengths
     for b in range(B):
         n = lengths[b]
@@ -185,7 +190,8 @@ def test_compress_token_list_and_strides(ctx):
     p.fit(Kd, int(n_keep.max()), tok_idx=ti, tok_off=to)
     p.compress(Kd, int(n_keep.max()), V_dev=Vd, tok_idx=ti, tok_off=to)
     assert p.seq_len.cpu().tolist() == n_keep.tolist()
-    cov, mu, Kt, Rr, Vc = to_host(p.cov), to_host(p.mu), to_host(p.Kp), to_host(p.Rr), to_host(p.Vc)
+    cov, mu, Rr = to_host(p.cov), to_host(p.mu), to_host(p.Rr)
+    Kt, Vc = p.unpacked()
     for b in range(B):
         rows = tok_idx[tok_off[b]:tok_off[b + 1]]
         for h in range(Hkv):
@@ -263,7 +269,7 @@ def test_append_then_decode(ctx):
     for step in range(12):
         new = layer(B, Hq, Hkv, 1, dtype, 1700 + step)
         p.append(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype))
-        Kt, Vc = to_host(p.Kp), to_host(p.Vc)
+        Kt, Vc = p.unpacked()
         for b in range(B):
             for h in range(Hkv):
                 check_packed(Kt[b, h, lens[b]:lens[b] + 1], new["k_new"][b, h][None].astype(np.float64), Rr[b, h], dtype)
@@ -285,12 +291,13 @@ def test_append_device_guard(ctx):
     B, Hkv, r, dtype, cap = 2, 2, 32, "bf16", 64
     data = layer(B, Hkv, Hkv, cap, dtype, 18, lengths=[64, 10])
     p = run_prefill(ctx, data, B, Hkv, Hkv, cap, r, dtype, lengths=[64, 10], cap=cap)
-    before = to_host(p.Kp).copy()
+    assert p.cap == cap
+    before = p.unpacked()[0].copy()
     p.max_seq_len = 10                      # host bound of the short sequence only
     new = layer(B, Hkv, Hkv, 1, dtype, 1800)
     p.append(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype))
     assert p.seq_len.cpu().tolist() == [64, 11]
-    after = to_host(p.Kp)
+    after = p.unpacked()[0]
     assert np.array_equal(after[0], before[0])
     assert after[1, :, 10].any()
 
@@ -327,7 +334,7 @@ def test_full_size_gqa_16k(ctx):
     cov = to_host(p.cov)
     mu_o, C_o = oracle.mean_scatter(data["K"][5, 2])
     assert rel_max(cov[5, 2], C_o) <= TOL_F32
-    Kt, Rr = to_host(p.Kp), to_host(p.Rr)
+    Kt, Rr = p.unpacked()[0], to_host(p.Rr)
     for (b, h) in ((0, 0), (7, 3)):
         sel = np.r_[0:40, 8000:8040, 16344:16384]
         check_packed(Kt[b, h][sel], data["K"][b, h][sel].astype(np.float64), Rr[b, h], dtype)
