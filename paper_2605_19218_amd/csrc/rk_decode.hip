@@ -108,28 +108,35 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
     const float* a = ws_acc + row * S * D + tid;
-    float M = NEG_INF;
-    for (int i = 0; i < S; ++i) M = fmaxf(M, m[i]);
-    float o = 0.f;
-    if (M > NEG_INF) {
-        float den = 0.f, num = 0.f;
-        int i = 0;
-        for (; i + 8 <= S; i += 8) {
-            float av[8], wv[8];
+    // online over chunks of 16 partials: the 48 loads of a chunk are independent of each other
+    // and of the running maximum, so one memory round trip serves a whole chunk
+    float M = NEG_INF, den = 0.f, num = 0.f;
+    for (int i0 = 0; i0 < S; i0 += 16) {
+        float av[16], mv[16], lv[16];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) av[k] = a[(size_t)(i + k) * D];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) wv[k] = exp2f(m[i + k] - M);       // 2^(-inf) = 0 for empty splits
-#pragma unroll
-            for (int k = 0; k < 8; ++k) { den = fmaf(l[i + k], wv[k], den); num = fmaf(av[k], wv[k], num); }
+        for (int k = 0; k < 16; ++k) {
+            const bool in = i0 + k < S;
+            av[k] = in ? a[(size_t)(i0 + k) * D] : 0.f;
+            mv[k] = in ? m[i0 + k] : NEG_INF;
+            lv[k] = in ? l[i0 + k] : 0.f;
         }
-        for (; i < S; ++i) {
-            float w = exp2f(m[i] - M);
-            den = fmaf(l[i], w, den);
-            num = fmaf(a[(size_t)i * D], w, num);
+        float Mc = M;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) Mc = fmaxf(Mc, mv[k]);
+        if (Mc > NEG_INF) {
+            const float resc = exp2f(M - Mc);           // 0 on the first non-empty chunk
+            den *= resc;
+            num *= resc;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                float w = exp2f(mv[k] - Mc);            // 2^(-inf) = 0 for empty splits
+                den = fmaf(lv[k], w, den);
+                num = fmaf(av[k], w, num);
+            }
+            M = Mc;
         }
-        o = num / den;
     }
+    const float o = (M > NEG_INF) ? num / den : 0.f;
     st_elem(out + row * D + tid, o);
 }
 
@@ -270,6 +277,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     __shared__ float qs[16][D];
     __shared__ float qt[16][R];
     __shared__ float sbias[16];
+    __shared__ float sdm[D];
     __shared__ float sm_m[4][16], sm_l[4][16];
 
     const int G = Hq / Hkv;
@@ -291,7 +299,28 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         const bf16_t* Vu = Vc + (size_t)u * cap * D;
         const int ntiles = (t1 - t0 + 31) >> 5;
 
-        // two tiles of loads go out before the prologue so HBM latency overlaps it
+        // ---- prologue loads first: q (16 B per thread), this thread's R_r column pieces and
+        // delta_mu go out before anything else, so they are served by an idle memory system
+        // in ONE round trip instead of queueing behind the tile prefetches of every wave.
+        constexpr int NPASS = (4 * R + 255) / 256;     // (channel quarter, column) items per thread
+        const float* Ru = Rr + (size_t)u * D * R;
+        uint4 qraw = make_uint4(0, 0, 0, 0);
+        {
+            const int hh = tid >> 4;
+            if (hh < Gc) qraw = *(const uint4*)(q + ((size_t)b * Hq + h0 + hh) * D + (tid & 15) * 8);
+        }
+        float xr[NPASS][32];
+#pragma unroll
+        for (int pss = 0; pss < NPASS; ++pss) {
+            const int idx = tid + 256 * pss;
+            const int cq = idx / R, j = idx - cq * R;
+#pragma unroll
+            for (int c = 0; c < 32; ++c) xr[pss][c] = (idx < 4 * R) ? Ru[(32 * cq + c) * R + j] : 0.f;
+        }
+        float dmv = 0.f;
+        if (dmu && tid < D) dmv = dmu[(size_t)u * D + tid];
+
+        // then two tiles of K~/V per wave, in flight while q~ is computed
         Tile TA, TB;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
@@ -308,41 +337,46 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
             TA.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
             TB.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
         }
-        if (wave < ntiles) load_tile<R>(TA, Ku, Vu, t0 + wave * 32, lane);
-        if (wave + 4 < ntiles) load_tile<R>(TB, Ku, Vu, t0 + (wave + 4) * 32, lane);
+        // this wave's tiles are wave, wave + 4, ...: nk of them; tile k starts at tokA + 128 k
+        const int nk = (ntiles - wave + 3) >> 2;
+        const int tokA = t0 + wave * 32;
+        if (nk > 0) load_tile<R>(TA, Ku, Vu, tokA, lane);
+        if (nk > 1) load_tile<R>(TB, Ku, Vu, tokA + 128, lane);
 
-        // ---- prologue: q~ = q R_r scaled into the log2 domain, and the bias ------------
-        for (int idx = tid; idx < 16 * D; idx += 256) {
-            int hh = idx >> 7, c = idx & 127;
-            qs[hh][c] = hh < Gc ? bf16_to_f32(q[((size_t)b * Hq + h0 + hh) * D + c]) : 0.f;
+        // ---- q~ = q R_r scaled into the log2 domain, and the bias ----------------------
+        {
+            const int hh = tid >> 4, c0 = (tid & 15) * 8;
+            const uint32_t w[4] = {qraw.x, qraw.y, qraw.z, qraw.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                qs[hh][c0 + 2 * e] = __uint_as_float(w[e] << 16);
+                qs[hh][c0 + 2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+            }
+            if (tid < D) sdm[tid] = dmv;
         }
         __syncthreads();
-        {
-            // item (cq, j): partial sums over channels [32 cq, 32 cq + 32) for all heads;
-            // the 32 loads of R_r are independent, so one memory round trip covers them
-            const float* Ru = Rr + (size_t)u * D * R;
-            for (int idx = tid; idx < 4 * R; idx += 256) {
-                int cq = idx / R, j = idx - cq * R;
-                float x[32];
+        // item (cq, j): partial sums over channels [32 cq, 32 cq + 32) for every head
 #pragma unroll
-                for (int c = 0; c < 32; ++c) x[c] = Ru[(32 * cq + c) * R + j];
+        for (int pss = 0; pss < NPASS; ++pss) {
+            const int idx = tid + 256 * pss;
+            if (idx < 4 * R) {
+                const int cq = idx / R, j = idx - cq * R;
                 for (int hh = 0; hh < 16; ++hh) {
                     float a = 0.f;
                     if (hh < Gc) {
 #pragma unroll
-                        for (int c = 0; c < 32; ++c) a = fmaf(qs[hh][32 * cq + c], x[c], a);
+                        for (int c = 0; c < 32; ++c) a = fmaf(qs[hh][32 * cq + c], xr[pss][c], a);
                     }
                     big[(cq * 16 + hh) * R + j] = a;
                 }
             }
-            if (tid < 16) {
-                float a = 0.f;
-                if (tid < Gc && dmu) {
-                    const float* dm = dmu + (size_t)u * D;
-                    for (int c = 0; c < D; ++c) a = fmaf(qs[tid][c], dm[c], a);
-                }
-                sbias[tid] = a * scale_log2;
+        }
+        if (tid < 16) {
+            float a = 0.f;
+            if (tid < Gc) {
+                for (int c = 0; c < D; ++c) a = fmaf(qs[tid][c], sdm[c], a);
             }
+            sbias[tid] = a * scale_log2;
         }
         __syncthreads();
         for (int idx = tid; idx < 16 * R; idx += 256) {
@@ -387,49 +421,94 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) st.O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-        for (int tile = wave; tile < ntiles; tile += 8) {
-            compute_tile<R>(TA, st, qh, ql, qth, qtl, t0 + tile * 32, t1, g);
-            if (tile + 8 < ntiles) load_tile<R>(TA, Ku, Vu, t0 + (tile + 8) * 32, lane);
-            if (tile + 4 < ntiles) {
-                compute_tile<R>(TB, st, qh, ql, qth, qtl, t0 + (tile + 4) * 32, t1, g);
-                if (tile + 12 < ntiles) load_tile<R>(TB, Ku, Vu, t0 + (tile + 12) * 32, lane);
-            }
+        // Steady state: two tiles of loads always in flight behind the tile being computed.
+        // No branch around the loads here, so the compiler's outstanding-load counts
+        // (s_waitcnt vmcnt) are exact and a wave never waits for its newest prefetch.
+        int k = 0;
+        for (; k + 3 < nk; k += 2) {
+            compute_tile<R>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g);
+            load_tile<R>(TA, Ku, Vu, tokA + 128 * (k + 2), lane);
+            compute_tile<R>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g);
+            load_tile<R>(TB, Ku, Vu, tokA + 128 * (k + 3), lane);
         }
+        // tail: up to three tiles left (A, B, A)
+        if (k < nk) {
+            compute_tile<R>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g);
+            if (k + 2 < nk) load_tile<R>(TA, Ku, Vu, tokA + 128 * (k + 2), lane);
+        }
+        if (k + 1 < nk) compute_tile<R>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g);
+        if (k + 2 < nk) compute_tile<R>(TA, st, qh, ql, qth, qtl, tokA + 128 * (k + 2), t1, g);
 
         // ---- merge the four waves' states ----------------------------------------------
+        // Every wave holds O in the same lane layout, so the exchange is lane-to-lane: each
+        // lane parks its 8 accumulator quads in LDS ([wave][cb][lane], 128-bit, conflict
+        // free); wave w then folds channel blocks 2w, 2w+1 of all four waves and stores the
+        // result straight from the MFMA layout (lane (g, n): heads 4g..4g+3, channel 16cb+n).
         float l_run = st.l_run;
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
-        float* ow = big + wave * (16 * D);        // [16 heads][128 channels]
+        f32x4* park = (f32x4*)big;                 // [4 waves][8 cb][64 lanes]
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb)
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) ow[(4 * g + ii) * D + 16 * cb + n] = st.O[cb][ii];
+        for (int cb = 0; cb < 8; ++cb) park[(wave * 8 + cb) * 64 + lane] = st.O[cb];
         if (g == 0) { sm_m[wave][n] = st.m_run; sm_l[wave][n] = l_run; }
-    }
-    __syncthreads();
+        __syncthreads();
 
-    // ---- the split's result: straight to `out` if it is the only split, else a partial ----
-    for (int idx = tid; idx < Gc * D; idx += 256) {
-        int hh = idx >> 7, c = idx & 127;
-        const size_t row = (size_t)b * Hq + h0 + hh;
-        float M = NEG_INF, lsum = 0.f, a = 0.f;
-        if (!empty) {
-            M = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
+        f32x4 wgt[4];                              // weight of wave w for heads 4g + ii
+        f32x4 Mh, lh = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const int hh = 4 * g + ii;
+            float M = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
+            Mh[ii] = M;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 float mw = sm_m[w][hh];
-                float wgt = (mw > NEG_INF) ? fast_exp2(mw - M) : 0.f;
-                lsum = fmaf(sm_l[w][hh], wgt, lsum);
-                a = fmaf(big[(w * 16 + hh) * D + c], wgt, a);
+                float x = (mw > NEG_INF) ? fast_exp2(mw - M) : 0.f;
+                wgt[w][ii] = x;
+                lh[ii] = fmaf(sm_l[w][hh], x, lh[ii]);
             }
         }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int cb = 2 * wave + k;
+            f32x4 acc = park[(0 * 8 + cb) * 64 + lane] * wgt[0];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) acc += park[(w * 8 + cb) * 64 + lane] * wgt[w];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                const int hh = 4 * g + ii;
+                if (hh < Gc) {
+                    const size_t row = (size_t)b * Hq + h0 + hh;
+                    const int c = 16 * cb + n;
+                    if (S == 1) out[row * D + c] = f32_to_bf16(acc[ii] / lh[ii]);
+                    else ws_acc[(row * S + split) * D + c] = acc[ii];
+                }
+            }
+        }
+        if (S > 1 && wave == 0 && n == 0) {        // lanes (g, 0): m and l of heads 4g..4g+3
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                const int hh = 4 * g + ii;
+                if (hh < Gc) {
+                    const size_t pidx = ((size_t)b * Hq + h0 + hh) * S + split;
+                    ws_m[pidx] = Mh[ii] + sbias[hh];
+                    ws_l[pidx] = lh[ii];
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- empty split: zeros with m = -inf (or zeros to `out` if it is the only split) ----
+    for (int idx = tid; idx < Gc * D; idx += 256) {
+        int hh = idx >> 7, c = idx & 127;
+        const size_t row = (size_t)b * Hq + h0 + hh;
         if (S == 1) {
-            out[row * D + c] = f32_to_bf16(empty ? 0.f : a / lsum);
+            out[row * D + c] = f32_to_bf16(0.f);
         } else {
             const size_t pidx = row * S + split;
-            ws_acc[pidx * D + c] = a;                   // an empty split stores zeros with m = -inf
-            if (c == 0) { ws_m[pidx] = empty ? NEG_INF : M + sbias[hh]; ws_l[pidx] = lsum; }
+            ws_acc[pidx * D + c] = 0.f;
+            if (c == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
         }
     }
 }
