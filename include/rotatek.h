@@ -113,6 +113,7 @@ typedef struct {
     float* mu;           /* [B,H_kv,d]    per-head channel mean of the fitted Keys             */
     float* delta_mu;     /* [B,H_kv,d]    mu - R_r R_r^T mu  (Alg. 1 step 15)                   */
     float* cov;          /* optional [B,H_kv,d,d]: the un-weighted scatter of Alg. 1 step 3     */
+    int32_t* sweeps;     /* optional [B,H_kv] (int32): Jacobi sweeps the eigensolver used        */
 } rk_fit_out;
 
 /* ---- context ------------------------------------------------------------- */

@@ -44,7 +44,8 @@ class rk_rows(C.Structure):
 
 class rk_fit_out(C.Structure):
     _fields_ = [("R", C.c_void_p), ("eigvals", C.c_void_p), ("mask", C.c_void_p), ("keep_idx", C.c_void_p),
-                ("R_r", C.c_void_p), ("mu", C.c_void_p), ("delta_mu", C.c_void_p), ("cov", C.c_void_p)]
+                ("R_r", C.c_void_p), ("mu", C.c_void_p), ("delta_mu", C.c_void_p), ("cov", C.c_void_p),
+                ("sweeps", C.c_void_p)]
 
 
 class RotateKError(RuntimeError):
@@ -164,10 +165,11 @@ class FitOut:
     mu: Any
     delta_mu: Any
     cov: Any = None
+    sweeps: Any = None
 
     def c(self) -> rk_fit_out:
         return rk_fit_out(*[_ptr(getattr(self, f)) for f in
-                            ("R", "eigvals", "mask", "keep_idx", "R_r", "mu", "delta_mu", "cov")])
+                            ("R", "eigvals", "mask", "keep_idx", "R_r", "mu", "delta_mu", "cov", "sweeps")])
 
 
 # ---- the ABI, same names -----------------------------------------------------

@@ -270,7 +270,9 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const int B = L->batch, Hkv = L->n_kv_heads, U = B * Hkv;
-    const int nc = cov_chunks(keys->n_tokens);
+    const int ct = cov_chunk_tokens(L->dtype, !ctx->force_generic);
+    int nc = (keys->n_tokens + ct - 1) / ct;        // never more than the workspace was sized for
+    if (nc < 1) nc = 1;
     char* ws = (char*)workspace;
     float* part_S = (float*)(ws + w.part_S);
     float* part_sum = (float*)(ws + w.part_sum);
@@ -279,10 +281,11 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     hipStream_t st = as_stream(stream);
     e = launch_cov_partial(L->dtype, !ctx->force_generic, rows, B, Hkv, nc, part_S, part_sum, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "covariance launch");
-    e = launch_cov_finalize(rows, B, Hkv, nc, (flags & RK_FIT_CENTER) != 0, part_S, part_sum, cov, out->mu, st);
+    e = launch_cov_finalize(rows, B, Hkv, nc, (flags & RK_FIT_CENTER) != 0, ct == cov_chunk_tokens(RK_BF16, true),
+                            part_S, part_sum, cov, out->mu, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "covariance reduction launch");
     e = launch_eig(U, cov, sigma, out->mu, L->keep, out->R, out->eigvals, out->mask, out->keep_idx, out->R_r,
-                   out->delta_mu, st);
+                   out->delta_mu, out->sweeps, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "eigensolver launch");
     return RK_OK;
 }

@@ -67,7 +67,7 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
     return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
-template <int R>
+template <int R, bool GATHER>
 __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int cap,
                                                      const float* __restrict__ Rr, bf16_t* __restrict__ Kp,
                                                      int32_t* __restrict__ seq_len_out)
@@ -106,6 +106,8 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
     __syncthreads();
 
     const bf16_t* base = (const bf16_t*)rows.data;
+    const int64_t hb = (int64_t)b * rows.sb + (int64_t)h * rows.sh;
+    const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
     const int w0 = blk0 + wave * (Cfg::TT * 16);
     if (w0 >= n_b) return;
 
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
 #pragma unroll
     for (int tt = 0; tt < Cfg::TT; ++tt) {
         int tok = min(w0 + tt * 16 + n, n_b - 1);
-        const bf16_t* row = base + rows_offset(rows, b, h, tok);
+        const bf16_t* row = base + row_off<GATHER>(hb, rows.st, list, tok);
 #pragma unroll
         for (int i = 0; i < 4; ++i) kb[tt][i] = *(const bf16x8*)(row + 32 * i + 8 * g);
     }
@@ -207,11 +209,13 @@ __global__ __launch_bounds__(256) void v_retile(RowsDev rows, int Hkv, int cap, 
 }
 
 // ---------------------------------------------------------------------------
-// Append: block (h, b), 128 threads.  k~_j = sum_c k_new[c] R_r[c][j].  The block
-// that finishes last for a batch item bumps its length (all blocks of the item
-// read the old length before taking a ticket).
+// Append: block (h, b), 256 threads.  k~_j = sum_c k_new[c] R_r[c][j]: thread (cq, j)
+// sums one quarter of the channels (its 32 loads of R_r are independent, one memory
+// round trip), the four quarters are added in a fixed order.  The block that
+// finishes last for a batch item bumps its length (all blocks of the item read the
+// old length before taking a ticket).
 template <typename T>
-__global__ __launch_bounds__(128) void append_rows(int Hkv, int cap, int r, const T* __restrict__ k_new,
+__global__ __launch_bounds__(256) void append_rows(int Hkv, int cap, int r, const T* __restrict__ k_new,
                                                    const T* __restrict__ v_new, const float* __restrict__ Rr,
                                                    T* __restrict__ Kp, T* __restrict__ Vc,
                                                    int32_t* __restrict__ seq_len, int32_t* __restrict__ tickets)
@@ -221,17 +225,29 @@ __global__ __launch_bounds__(128) void append_rows(int Hkv, int cap, int r, cons
     const int len = seq_len[b];
     const bool ok = len >= 0 && len < cap;
     __shared__ float kn[D];
+    __shared__ float part[4][D];
     if (ok) {
         const int rp = keep_padded(r);
-        kn[tid] = ld_elem(k_new + (size_t)u * D + tid);
-        __syncthreads();
-        if (tid < r) {
-            const float* Ru = Rr + (size_t)u * D * r;
+        const float* Ru = Rr + (size_t)u * D * r;
+        if (tid < D) kn[tid] = ld_elem(k_new + (size_t)u * D + tid);
+        const int npass = (4 * r + 255) / 256;                   // 1 or 2, the same for every thread
+        for (int pss = 0; pss < npass; ++pss) {
+            const int idx = tid + 256 * pss;
+            const bool act = idx < 4 * r;
+            const int cq = act ? idx / r : 0, j = act ? idx - cq * r : 0;
+            float x[32];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) x[c] = act ? Ru[(32 * cq + c) * r + j] : 0.f;
+            if (pss == 0) __syncthreads();                       // kn staged (uniform branch)
             float a = 0.f;
-            for (int c = 0; c < D; ++c) a = fmaf(kn[c], Ru[c * r + tid], a);
-            st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp), a);
+#pragma unroll
+            for (int c = 0; c < 32; ++c) a = fmaf(kn[32 * cq + c], x[c], a);
+            if (act) part[cq][j] = a;
         }
-        Vc[(size_t)u * cap * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
+        __syncthreads();
+        if (tid < r) st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp),
+                             (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]));
+        if (tid < D) Vc[(size_t)u * cap * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
     }
     __syncthreads();
     if (tid == 0) {
@@ -275,8 +291,12 @@ static hipError_t launch_compress_mfma_r(const RowsDev& rows, int B, int Hkv, in
     typedef CompressCfg<R> Cfg;
     int nblk = (rows.n_tokens + Cfg::TOK_PER_BLOCK - 1) / Cfg::TOK_PER_BLOCK;
     if (nblk < 1) nblk = 1;
-    hipLaunchKernelGGL(compress_mfma<R>, dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv, cap, Rr,
-                       Kp, seq_len_out);
+    if (rows.tok_idx)
+        hipLaunchKernelGGL((compress_mfma<R, true>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
+                           cap, Rr, Kp, seq_len_out);
+    else
+        hipLaunchKernelGGL((compress_mfma<R, false>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
+                           cap, Rr, Kp, seq_len_out);
     return hipGetLastError();
 }
 
@@ -324,10 +344,10 @@ hipError_t launch_append(int dtype, int B, int Hkv, int cap, int r, const void* 
 {
     dim3 grid(Hkv, B);
     if (dtype == 0)
-        hipLaunchKernelGGL(append_rows<float>, grid, dim3(128), 0, st, Hkv, cap, r, (const float*)k_new,
+        hipLaunchKernelGGL(append_rows<float>, grid, dim3(256), 0, st, Hkv, cap, r, (const float*)k_new,
                            (const float*)v_new, Rr, (float*)Kp, (float*)Vc, seq_len, tickets);
     else
-        hipLaunchKernelGGL(append_rows<bf16_t>, grid, dim3(128), 0, st, Hkv, cap, r, (const bf16_t*)k_new,
+        hipLaunchKernelGGL(append_rows<bf16_t>, grid, dim3(256), 0, st, Hkv, cap, r, (const bf16_t*)k_new,
                            (const bf16_t*)v_new, Rr, (bf16_t*)Kp, (bf16_t*)Vc, seq_len, tickets);
     return hipGetLastError();
 }

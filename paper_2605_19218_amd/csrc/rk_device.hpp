@@ -9,6 +9,7 @@ constexpr int D = 128;                 // head dim the kernels are written for
 typedef uint16_t bf16_t;               // raw bfloat16 storage
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -62,6 +63,14 @@ __device__ __forceinline__ int rows_count(const RowsDev& r, int b) {
 __device__ __forceinline__ int64_t rows_offset(const RowsDev& r, int b, int h, int t) {
     int64_t row = r.tok_idx ? (int64_t)r.tok_idx[r.tok_off[b] + t] : (int64_t)t;
     return (int64_t)b * r.sb + (int64_t)h * r.sh + row * r.st;
+}
+// Branch-free form for the streaming kernels (GATHER is a template parameter there, so a
+// sequence of row loads stays one basic block and the load counters are tracked exactly).
+// head_base = b * sb + h * sh, list = tok_idx + tok_off[b].
+template <bool GATHER>
+__device__ __forceinline__ int64_t row_off(int64_t head_base, int64_t st, const int32_t* __restrict__ list, int t) {
+    const int64_t row = GATHER ? (int64_t)list[t] : (int64_t)t;
+    return head_base + row * st;
 }
 
 // ---------------------------------------------------------------------------

@@ -72,10 +72,234 @@ __global__ __launch_bounds__(256) void cov_partial_generic(RowsDev rows, int Hkv
 }
 
 // ---------------------------------------------------------------------------
+// MFMA covariance partial (bf16 Keys): S = K^T K over a 2048-token chunk with
+// v_mfma_f32_32x32x16_bf16, contraction index = tokens.  The matrix core wants, per
+// lane, 8 consecutive TOKENS of one channel, while memory holds 8 consecutive
+// CHANNELS of one token.  No LDS staging is used: lane (g2, m) loads the 8x8 block
+// (tokens 8 g2 ..+7) x (channels 8 (m%16) ..+7) as eight 16-byte row pieces and
+// transposes it in registers with v_perm; lanes m and m+16 share a block and take
+// the even / odd channels of it.  The channel held by MFMA row m of block cbk is
+// therefore ch(cbk, m) = 8 (m % 16) + 2 cbk + m / 16 -- a permutation that is undone
+// when the 128x128 partial is written.  Each wave accumulates the 10 upper-triangular
+// 32x32 tiles for its own 512 tokens (160 accumulator registers); the four waves are
+// summed through LDS in a fixed order.
+constexpr int COVM_TOK_PER_WAVE = 512;
+constexpr int COVM_CHUNK = 4 * COVM_TOK_PER_WAVE;
+constexpr int COVM_STAGES = 6;             // 16-token k-steps of loads in flight per wave
+constexpr size_t COVM_LDS_BYTES = (size_t)(2 * 10 * 16 * 64 + 4 * D) * sizeof(float);   // 2 parked sets + column sums
+
+// rows >= t_end contribute zeros; the address is clamped to row t_last (always a valid row)
+// all 8 rows known to be valid: plain loads, nothing for the compiler to predicate.  Without
+// a token list the row address is lane_ptr + (tok0 + jj) * st with st wave-uniform, so the
+// only per-lane work is one 64-bit add per row (no per-lane 64-bit multiplies).
+template <bool GATHER>
+__device__ __forceinline__ void covm_load_full(uint4 (&r)[8], const bf16_t* __restrict__ base, int64_t head_base,
+                                               int64_t st, const int32_t* __restrict__ list, int tok0, int o,
+                                               const bf16_t* __restrict__ lane_ptr, int tok_rel)
+{
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+        if (GATHER) r[jj] = *(const uint4*)(base + row_off<true>(head_base, st, list, tok0 + jj) + 8 * o);
+        else r[jj] = *(const uint4*)(lane_ptr + (int64_t)(tok_rel + jj) * st);
+    }
+}
+
+template <bool GATHER>
+__device__ __forceinline__ void covm_load(uint4 (&r)[8], const bf16_t* __restrict__ base, int64_t head_base,
+                                          int64_t st, const int32_t* __restrict__ list, int tok0, int t_end,
+                                          int t_last, int o)
+{
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+        const int tok = tok0 + jj;
+        const uint4 v = *(const uint4*)(base + row_off<GATHER>(head_base, st, list, min(tok, t_last)) + 8 * o);
+        r[jj] = tok < t_end ? v : make_uint4(0, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ uint32_t dw(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+__device__ __forceinline__ void covm_step(const uint4 (&r)[8], uint32_t sel, f32x16 (&acc)[10], float (&csum)[4])
+{
+    bf16x8 frag[4];
+#pragma unroll
+    for (int cbk = 0; cbk < 4; ++cbk) {
+        uint4 d;
+        // token pair (2 tp, 2 tp + 1) of channel 2 cbk + parity: low or high halves of dword cbk
+        d.x = __builtin_amdgcn_perm(dw(r[1], cbk), dw(r[0], cbk), sel);
+        d.y = __builtin_amdgcn_perm(dw(r[3], cbk), dw(r[2], cbk), sel);
+        d.z = __builtin_amdgcn_perm(dw(r[5], cbk), dw(r[4], cbk), sel);
+        d.w = __builtin_amdgcn_perm(dw(r[7], cbk), dw(r[6], cbk), sel);
+        frag[cbk] = __builtin_bit_cast(bf16x8, d);
+        // column sums: v_dot2 of each token pair with (1, 1), fp32 accumulate
+        const bf16x2 one2 = {(__bf16)1.0f, (__bf16)1.0f};
+        float s = csum[cbk];
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, d.x), one2, s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, d.y), one2, s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, d.z), one2, s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, d.w), one2, s, false);
+        csum[cbk] = s;
+    }
+    int t = 0;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = bi; bj < 4; ++bj) {
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[bi], frag[bj], acc[t], 0, 0, 0);
+            ++t;
+        }
+}
+
+template <bool GATHER>
+__global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, int n_chunks,
+                                                        float* __restrict__ part_S, float* __restrict__ part_sum)
+{
+    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int u = b * Hkv + h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: loop control stays scalar
+    const int g2 = lane >> 5, m = lane & 31, o = m & 15, par = m >> 4;
+    const uint32_t sel = par ? 0x07060302u : 0x05040100u;
+    const int n_b = rows_count(rows, b);
+    const int t0 = chunk * COVM_CHUNK, t1 = min(t0 + COVM_CHUNK, n_b);
+    const int tw0 = t0 + wave * COVM_TOK_PER_WAVE, tw1 = min(tw0 + COVM_TOK_PER_WAVE, t1);
+    const int nks = tw1 > tw0 ? (tw1 - tw0 + 15) >> 4 : 0;      // 16-token k-steps, the last may be partial
+    const int nfull = tw1 > tw0 ? (tw1 - tw0) >> 4 : 0;         // k-steps with all 16 tokens valid
+    const bf16_t* base = (const bf16_t*)rows.data;
+    const int64_t hb = (int64_t)b * rows.sb + (int64_t)h * rows.sh, rst = rows.st;
+    const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
+    // this lane's first row piece: token tw0 + 8 g2, channels 8 o ..+7 (used when there is no token list)
+    const bf16_t* lane_ptr = base + hb + (int64_t)(tw0 + 8 * g2) * rst + 8 * o;
+
+    extern __shared__ __attribute__((aligned(16))) float cov_smem[];
+    f32x4* bufv = (f32x4*)cov_smem;             // two parked accumulator sets: [2][tile][i / 4][lane]
+    float (*ssum)[D] = (float (*)[D])(cov_smem + 2 * 10 * 16 * 64);
+
+    f32x16 acc[10];
+#pragma unroll
+    for (int t = 0; t < 10; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    float csum[4] = {0.f, 0.f, 0.f, 0.f};
+
+    if (nks > 0) {
+        uint4 st[COVM_STAGES][8];
+        int ks = 0;
+        // Every wave owns a 128 KB run of rows at a 128 KB-aligned offset; walking them all from
+        // the start would keep the 1024 waves of the grid on the same few HBM channels at any
+        // instant.  A full wave (32 k-steps) therefore starts at a wave/chunk/head dependent
+        // k-step and wraps around (the sum is order-independent up to fp32 rounding, and the
+        // order is still fixed for a given launch shape).
+        constexpr int NKW = COVM_TOK_PER_WAVE / 16;
+        const int shift = (nfull == NKW) ? ((wave * 8 + chunk * 5 + u * 11) & (NKW - 1)) : 0;
+#define KSTEP_TOK(i) (16 * (((i) + shift) & (NKW - 1)))
+        if (nfull >= 2 * COVM_STAGES) {
+            // Long chunk (the normal case).  The fill and the steady loop use plain loads of
+            // full k-steps with no branch anywhere near them, so every wait on them is exact
+            // (a conservative wait-count state entering the loop would be paid every iteration).
+#pragma unroll
+            for (int s = 0; s < COVM_STAGES; ++s) {
+                covm_load_full<GATHER>(st[s], base, hb, rst, list, tw0 + KSTEP_TOK(s) + 8 * g2, o, lane_ptr, KSTEP_TOK(s));
+                __builtin_amdgcn_sched_barrier(0);      // stage 0 must be the OLDEST load on loop entry
+            }
+            for (; ks + 2 * COVM_STAGES <= nfull; ks += COVM_STAGES) {
+#pragma unroll
+                for (int s = 0; s < COVM_STAGES; ++s) {
+                    covm_step(st[s], sel, acc, csum);
+                    covm_load_full<GATHER>(st[s], base, hb, rst, list, tw0 + KSTEP_TOK(ks + s + COVM_STAGES) + 8 * g2, o,
+                                           lane_ptr, KSTEP_TOK(ks + s + COVM_STAGES));
+                    // keep "consume stage s, refill stage s" together: without this the scheduler
+                    // hoists all four stages' math above all 32 loads and the pipeline collapses
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < COVM_STAGES; ++s)
+                covm_load<GATHER>(st[s], base, hb, rst, list, tw0 + 16 * s + 8 * g2, s < nks ? tw1 : 0, tw1 - 1, o);
+        }
+        // remaining k-steps (at most 2 STAGES - 1 after a steady loop), the last possibly partial
+        for (; ks < nks; ks += COVM_STAGES) {
+#pragma unroll
+            for (int s = 0; s < COVM_STAGES; ++s) {
+                if (ks + s < nks) {
+                    covm_step(st[s], sel, acc, csum);
+                    if (ks + s + COVM_STAGES < nks)
+                        covm_load<GATHER>(st[s], base, hb, rst, list,
+                                          tw0 + (shift ? KSTEP_TOK(ks + s + COVM_STAGES) : 16 * (ks + s + COVM_STAGES)) + 8 * g2,
+                                          tw1, tw1 - 1, o);
+                }
+            }
+        }
+    }
+
+#undef KSTEP_TOK
+
+    // ---- sum the four waves in a fixed order: ((w0 + w1) + w2) + w3 --------------------
+#pragma unroll
+    for (int cbk = 0; cbk < 4; ++cbk) {
+        float s = csum[cbk] + __shfl_xor(csum[cbk], 32);
+        if (g2 == 0) ssum[wave][8 * o + 2 * cbk + par] = s;
+    }
+    // (w0 + w1) + (w2 + w3), two phases, 128-bit LDS traffic
+    auto park = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 10; ++t)
+#pragma unroll
+            for (int iq = 0; iq < 4; ++iq)
+                bufv[(set * 40 + t * 4 + iq) * 64 + lane] =
+                    (f32x4){acc[t][4 * iq], acc[t][4 * iq + 1], acc[t][4 * iq + 2], acc[t][4 * iq + 3]};
+    };
+    auto add = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 10; ++t)
+#pragma unroll
+            for (int iq = 0; iq < 4; ++iq) {
+                const f32x4 v = bufv[(set * 40 + t * 4 + iq) * 64 + lane];
+                acc[t][4 * iq] += v[0]; acc[t][4 * iq + 1] += v[1]; acc[t][4 * iq + 2] += v[2]; acc[t][4 * iq + 3] += v[3];
+            }
+    };
+    if (wave == 1) park(0);
+    if (wave == 3) park(1);
+    __syncthreads();
+    if (wave == 0) add(0);
+    if (wave == 2) add(1);
+    __syncthreads();
+    if (wave == 2) park(0);
+    __syncthreads();
+    // wave 0 holds the chunk's sum; it stores the 10 upper-triangular tiles in register layout
+    // ([tile][i][lane], 40 KB, fully coalesced).  cov_finalize undoes the channel permutation
+    // and mirrors the lower triangle while it reduces over chunks.
+    if (wave == 0) {
+        add(0);
+        float* S = part_S + ((size_t)u * n_chunks + chunk) * (D * D);
+#pragma unroll
+        for (int t = 0; t < 10; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[(t * 16 + i) * 64 + lane] = acc[t][i];
+    }
+    __syncthreads();
+    if (tid < D)
+        part_sum[((size_t)u * n_chunks + chunk) * D + tid] = ((ssum[0][tid] + ssum[1][tid]) + ssum[2][tid]) + ssum[3][tid];
+}
+
+// ---------------------------------------------------------------------------
 // Reduce the chunk partials in fp64 and apply the centering correction
 // C = S - n mu mu^T (equal to (K-mu)^T (K-mu)).  grid (8, U): block x covers rows
 // [16x, 16x+16).
-__global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n_chunks, int center,
+// position of element (row channel, column channel) inside a tile-format partial written by
+// cov_partial_mfma: the 10 upper-triangular 32x32 MFMA tiles as [tile][i][lane]
+__device__ __forceinline__ int covm_tile_index(int rch, int cch)
+{
+    int br = (rch & 7) >> 1, mr = (rch >> 3) + 16 * (rch & 1);
+    int bc = (cch & 7) >> 1, mc = (cch >> 3) + 16 * (cch & 1);
+    if (br > bc) { int x = br; br = bc; bc = x; x = mr; mr = mc; mc = x; }
+    const int t = br * 4 - (br * (br - 1)) / 2 + (bc - br);
+    const int i = 4 * (mr >> 3) + (mr & 3), gg = (mr >> 2) & 1;
+    return (t * 16 + i) * 64 + 32 * gg + mc;
+}
+
+__global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n_chunks, int center, int tiled,
                                                     const float* __restrict__ part_S,
                                                     const float* __restrict__ part_sum,
                                                     float* __restrict__ cov, float* __restrict__ mu_out)
@@ -84,9 +308,22 @@ __global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n
     const int tid = threadIdx.x;
     const int n_b = rows_count(rows, b);
     __shared__ double smu[D];
-    if (tid < D) {
+    // sum over chunks in ascending order; loads are issued 8 at a time (independent), adds stay ordered
+    auto chunk_sum = [&](const float* __restrict__ p, size_t stride) {
         double s = 0.0;
-        for (int ch = 0; ch < n_chunks; ++ch) s += (double)part_sum[((size_t)u * n_chunks + ch) * D + tid];
+        int ch = 0;
+        for (; ch + 8 <= n_chunks; ch += 8) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = p[(size_t)(ch + k) * stride];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += (double)v[k];
+        }
+        for (; ch < n_chunks; ++ch) s += (double)p[(size_t)ch * stride];
+        return s;
+    };
+    if (tid < D) {
+        double s = chunk_sum(part_sum + (size_t)u * n_chunks * D + tid, D);
         double m = n_b > 0 ? s / (double)n_b : 0.0;
         smu[tid] = m;
         if (blockIdx.x == 0) mu_out[(size_t)u * D + tid] = (float)m;
@@ -95,9 +332,8 @@ __global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n
     const int j = tid & (D - 1);
     for (int ri = 0; ri < 8; ++ri) {
         int i = blockIdx.x * 16 + ri * 2 + (tid >> 7);
-        double s = 0.0;
-        for (int ch = 0; ch < n_chunks; ++ch)
-            s += (double)part_S[((size_t)u * n_chunks + ch) * (D * D) + i * D + j];
+        const int pos = tiled ? covm_tile_index(i, j) : i * D + j;
+        double s = chunk_sum(part_S + (size_t)u * n_chunks * (D * D) + pos, (size_t)D * D);
         if (center) s -= (double)n_b * (smu[i] * smu[j]);
         cov[(size_t)u * D * D + i * D + j] = (float)s;
     }
@@ -130,7 +366,8 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
                                                           float* __restrict__ R_out, float* __restrict__ lam_out,
                                                           uint8_t* __restrict__ mask_out,
                                                           int32_t* __restrict__ keep_out,
-                                                          float* __restrict__ Rr_out, float* __restrict__ dmu_out)
+                                                          float* __restrict__ Rr_out, float* __restrict__ dmu_out,
+                                                          int32_t* __restrict__ sweeps_out)
 {
     extern __shared__ float sm[];
     float* A = sm;                        // [128][128]
@@ -168,6 +405,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
     const float tol2 = (2e-8f * 2e-8f) * normF2;
     __syncthreads();
 
+    int sweeps_done = 0;
     for (int sweep = 0; sweep < EIG_MAX_SWEEPS; ++sweep) {
         // off-diagonal norm
         float off = 0.f;
@@ -183,6 +421,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
         for (int w = 0; w < 16; ++w) off2 += red[16 + w];
         __syncthreads();
         if (!(off2 > tol2)) break;      // uniform across the block
+        ++sweeps_done;
 
         for (int round = 0; round < D - 1; ++round) {
             if (tid < 64) {
@@ -246,6 +485,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
     }
 
     // ---- eigenvalues, rank, mask (integer logic), R, R_r, delta_mu -----------
+    if (tid == 0 && sweeps_out) sweeps_out[u] = sweeps_done;
     if (tid < D) slam[tid] = A[tid * D + tid];
     __syncthreads();
     if (tid < D) {
@@ -294,11 +534,31 @@ __global__ __launch_bounds__(256) void gather_rotation_kernel(int r, const float
 }
 
 // ---------------------------------------------------------------------------
+int cov_chunk_tokens(int dtype, bool mfma) { return (mfma && dtype == 1) ? COVM_CHUNK : COV_CHUNK; }
+
 hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int n_chunks,
                               float* part_S, float* part_sum, hipStream_t st)
 {
-    (void)mfma;
     dim3 grid(n_chunks, Hkv, B);
+    if (mfma && dtype == 1) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)cov_partial_mfma<true>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)COVM_LDS_BYTES);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute((const void*)cov_partial_mfma<false>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)COVM_LDS_BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        if (rows.tok_idx)
+            hipLaunchKernelGGL(cov_partial_mfma<true>, grid, dim3(256), COVM_LDS_BYTES, st, rows, Hkv, n_chunks, part_S,
+                               part_sum);
+        else
+            hipLaunchKernelGGL(cov_partial_mfma<false>, grid, dim3(256), COVM_LDS_BYTES, st, rows, Hkv, n_chunks,
+                               part_S, part_sum);
+        return hipGetLastError();
+    }
     if (dtype == 0)
         hipLaunchKernelGGL(cov_partial_generic<float>, grid, dim3(256), 0, st, rows, Hkv, n_chunks, part_S, part_sum);
     else
@@ -306,17 +566,18 @@ hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, 
     return hipGetLastError();
 }
 
-hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center,
+hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center, bool tiled,
                                const float* part_S, const float* part_sum, float* cov, float* mu,
                                hipStream_t st)
 {
     hipLaunchKernelGGL(cov_finalize, dim3(8, B * Hkv), dim3(256), 0, st, rows, Hkv, n_chunks, center ? 1 : 0,
-                       part_S, part_sum, cov, mu);
+                       tiled ? 1 : 0, part_S, part_sum, cov, mu);
     return hipGetLastError();
 }
 
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
-                      float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, hipStream_t st)
+                      float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
+                      hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -326,7 +587,7 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
         attr_set = true;
     }
     hipLaunchKernelGGL(eig_jacobi, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, mu, r, R, lam,
-                       mask, keep_idx, Rr, dmu);
+                       mask, keep_idx, Rr, dmu, sweeps);
     return hipGetLastError();
 }
 

@@ -7,15 +7,18 @@
 namespace rk {
 
 // ---- rk_fit.hip ------------------------------------------------------------
-// Tokens per covariance work-group; partials are [U, n_chunks, d*d] + [U, n_chunks, d].
-constexpr int COV_CHUNK = 512;
+// Partials are [U, n_chunks, d*d] + [U, n_chunks, d]; n_chunks = ceil(tokens / cov_chunk_tokens()).
+constexpr int COV_CHUNK = 512;             // tokens per work-group of the plain kernel (the smaller chunk)
+int cov_chunk_tokens(int dtype, bool mfma);
 hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int n_chunks,
                               float* part_S, float* part_sum, hipStream_t st);
-hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center,
+// tiled: the partials were written by the MFMA kernel (10 upper-triangular tiles in register layout)
+hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center, bool tiled,
                                const float* part_S, const float* part_sum, float* cov, float* mu,
                                hipStream_t st);
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
-                      float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, hipStream_t st);
+                      float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
+                      hipStream_t st);
 hipError_t launch_gather_rotation(int U, int r, const float* R, const int32_t* keep_idx, float* Rr,
                                   hipStream_t st);
 

@@ -59,6 +59,7 @@ class Pipeline:
         self.mu = torch.zeros(B, Hkv, D, **f32)
         self.dmu = torch.zeros(B, Hkv, D, **f32)
         self.cov = torch.zeros(B, Hkv, D, D, **f32)
+        self.sweeps = torch.zeros(B, Hkv, device=DEV, dtype=torch.int32)
         td = torch_dtype(dtype)
         self.seq_len = torch.zeros(B, device=DEV, dtype=torch.int32)
         self.max_seq_len = 0
@@ -86,7 +87,7 @@ class Pipeline:
     def fit(self, K_dev, n_tokens, sigma=None, center=True, n_dev=None, tok_idx=None, tok_off=None):
         lay = self.layout()
         ws = torch.empty(rk.rk_fit_workspace_size(lay, n_tokens), device=DEV, dtype=torch.uint8)
-        out = rk.FitOut(self.R, self.lam, self.mask, self.keep_idx, self.Rr, self.mu, self.dmu, self.cov)
+        out = rk.FitOut(self.R, self.lam, self.mask, self.keep_idx, self.Rr, self.mu, self.dmu, self.cov, self.sweeps)
         rk.rk_fit_rotation(self.ctx, lay, self.rows(K_dev, n_tokens, n_dev, tok_idx, tok_off), sigma,
                            rk.RK_FIT_CENTER if center else 0, out, ws)
         torch.cuda.synchronize()
