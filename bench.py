@@ -36,7 +36,23 @@ def parse():
     ap.add_argument("--keep", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times, so that a rocprofv3 --pmc run of this "
+                         "command records FETCH_SIZE / WRITE_SIZE of a kernel with known traffic")
     return ap.parse_args()
+
+
+def committed_traffic(kernel_tag):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc (FETCH_SIZE +
+    WRITE_SIZE, calibrated against a plain copy); read from the committed summary, None if absent."""
+    path = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_C3.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch[%s]:" % kernel_tag):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -189,6 +205,14 @@ def main():
             del stt
             torch.cuda.empty_cache()
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, device=dev, dtype=torch.uint8).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- the CPU oracle on the same workload (bounded sample) -------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -239,8 +263,9 @@ def main():
         "stages_us": stage_us,
         "decode_only_sweep": sweep,
         "roofline": {"bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "decode_fused_mfma<64> (rk_decode_attn, one launch)",
+                     "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": committed_traffic("decode_split_mfma<64>"),
+                     "kernel": "decode_split_mfma<64> + decode_merge (one rk_decode_attn call; the duration is the "
+                               "HIP-event time of the whole call on the launch stream)",
                      "algorithmic_bytes": decode_bytes(r_main, L + 1)},
         "roofline_compress": {"bound": "hbm", "achieved": comp_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": comp_gbps / HBM_PEAK_GBPS, "algorithmic_bytes": comp_bytes},
