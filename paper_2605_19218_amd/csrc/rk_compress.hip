@@ -55,7 +55,9 @@ struct CompressCfg {
     static constexpr int NF = R / 32;                 // full 32-channel groups
     static constexpr bool TAIL = (R % 32) != 0;       // one trailing 16-channel block
     static constexpr int TT = (R <= 64) ? 4 : 2;      // 16-token tiles in flight per wave
-    static constexpr int TOK_PER_BLOCK = 4 * TT * 16; // 4 waves
+    static constexpr int TOK_PER_PASS = 4 * TT * 16;  // tokens one pass of the 4 waves covers
+    static constexpr int PASSES = 4;                  // passes per work-group (amortises the R_r fragment build)
+    static constexpr int TOK_PER_BLOCK = PASSES * TOK_PER_PASS;
     static constexpr size_t LDS_BYTES = (size_t)JB * 4 * 2 * 64 * 16;   // A fragments, hi+lo
     // output channel held by A row a of block jb
     __host__ __device__ static constexpr int chan(int jb, int a) {
@@ -108,57 +110,60 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
     const bf16_t* base = (const bf16_t*)rows.data;
     const int64_t hb = (int64_t)b * rows.sb + (int64_t)h * rows.sh;
     const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
-    const int w0 = blk0 + wave * (Cfg::TT * 16);
-    if (w0 >= n_b) return;
+    bf16_t* Ku = Kp + (size_t)u * cap * R;
 
-    bf16x8 kb[Cfg::TT][4];
+    for (int pass = 0; pass < Cfg::PASSES; ++pass) {
+        const int w0 = blk0 + pass * Cfg::TOK_PER_PASS + wave * (Cfg::TT * 16);
+        if (w0 >= n_b) return;                      // later passes start even further right
+
+        bf16x8 kb[Cfg::TT][4];
 #pragma unroll
-    for (int tt = 0; tt < Cfg::TT; ++tt) {
-        int tok = min(w0 + tt * 16 + n, n_b - 1);
-        const bf16_t* row = base + row_off<GATHER>(hb, rows.st, list, tok);
+        for (int tt = 0; tt < Cfg::TT; ++tt) {
+            int tok = min(w0 + tt * 16 + n, n_b - 1);
+            const bf16_t* row = base + row_off<GATHER>(hb, rows.st, list, tok);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kb[tt][i] = *(const bf16x8*)(row + 32 * i + 8 * g);
-    }
-    f32x4 acc[Cfg::TT][Cfg::JB];
+            for (int i = 0; i < 4; ++i) kb[tt][i] = *(const bf16x8*)(row + 32 * i + 8 * g);
+        }
+        f32x4 acc[Cfg::TT][Cfg::JB];
 #pragma unroll
-    for (int tt = 0; tt < Cfg::TT; ++tt)
+        for (int tt = 0; tt < Cfg::TT; ++tt)
 #pragma unroll
-        for (int jb = 0; jb < Cfg::JB; ++jb) acc[tt][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int jb = 0; jb < Cfg::JB; ++jb) acc[tt][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
-    for (int jb = 0; jb < Cfg::JB; ++jb) {
+        for (int jb = 0; jb < Cfg::JB; ++jb) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            bf16x8 ah = frag[((jb * 4 + i) * 2 + 0) * 64 + lane];
-            bf16x8 al = frag[((jb * 4 + i) * 2 + 1) * 64 + lane];
+            for (int i = 0; i < 4; ++i) {
+                bf16x8 ah = frag[((jb * 4 + i) * 2 + 0) * 64 + lane];
+                bf16x8 al = frag[((jb * 4 + i) * 2 + 1) * 64 + lane];
 #pragma unroll
-            for (int tt = 0; tt < Cfg::TT; ++tt) {
-                acc[tt][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, kb[tt][i], acc[tt][jb], 0, 0, 0);
-                acc[tt][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb[tt][i], acc[tt][jb], 0, 0, 0);
+                for (int tt = 0; tt < Cfg::TT; ++tt) {
+                    acc[tt][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, kb[tt][i], acc[tt][jb], 0, 0, 0);
+                    acc[tt][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb[tt][i], acc[tt][jb], 0, 0, 0);
+                }
             }
         }
-    }
-    // lane (g, n): blocks 2i, 2i+1 hold channels 32 i + 8 g + (0..3), (4..7) of token w0 + 16 tt + n
-    bf16_t* Ku = Kp + (size_t)u * cap * R;
+        // lane (g, n): blocks 2i, 2i+1 hold channels 32 i + 8 g + (0..3), (4..7) of token w0 + 16 tt + n
 #pragma unroll
-    for (int tt = 0; tt < Cfg::TT; ++tt) {
-        int tok = w0 + tt * 16 + n;
-        if (tok < n_b) {
-            bf16_t* blk = Ku + (size_t)((w0 >> 4) + tt) * (16 * R);
+        for (int tt = 0; tt < Cfg::TT; ++tt) {
+            int tok = w0 + tt * 16 + n;
+            if (tok < n_b) {
+                bf16_t* blk = Ku + (size_t)((w0 >> 4) + tt) * (16 * R);
 #pragma unroll
-            for (int i = 0; i < Cfg::NF; ++i) {
-                uint4 pk;
-                pk.x = pack2_bf16(acc[tt][2 * i][0], acc[tt][2 * i][1]);
-                pk.y = pack2_bf16(acc[tt][2 * i][2], acc[tt][2 * i][3]);
-                pk.z = pack2_bf16(acc[tt][2 * i + 1][0], acc[tt][2 * i + 1][1]);
-                pk.w = pack2_bf16(acc[tt][2 * i + 1][2], acc[tt][2 * i + 1][3]);
-                *(uint4*)(blk + (4 * i) * 128 + lane * 8) = pk;
-            }
-            if (Cfg::TAIL) {
-                uint2 pk;
-                pk.x = pack2_bf16(acc[tt][Cfg::JB - 1][0], acc[tt][Cfg::JB - 1][1]);
-                pk.y = pack2_bf16(acc[tt][Cfg::JB - 1][2], acc[tt][Cfg::JB - 1][3]);
-                *(uint2*)(blk + (4 * Cfg::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1)) = pk;
+                for (int i = 0; i < Cfg::NF; ++i) {
+                    uint4 pk;
+                    pk.x = pack2_bf16(acc[tt][2 * i][0], acc[tt][2 * i][1]);
+                    pk.y = pack2_bf16(acc[tt][2 * i][2], acc[tt][2 * i][3]);
+                    pk.z = pack2_bf16(acc[tt][2 * i + 1][0], acc[tt][2 * i + 1][1]);
+                    pk.w = pack2_bf16(acc[tt][2 * i + 1][2], acc[tt][2 * i + 1][3]);
+                    *(uint4*)(blk + (4 * i) * 128 + lane * 8) = pk;
+                }
+                if (Cfg::TAIL) {
+                    uint2 pk;
+                    pk.x = pack2_bf16(acc[tt][Cfg::JB - 1][0], acc[tt][Cfg::JB - 1][1]);
+                    pk.y = pack2_bf16(acc[tt][Cfg::JB - 1][2], acc[tt][Cfg::JB - 1][3]);
+                    *(uint2*)(blk + (4 * Cfg::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1)) = pk;
+                }
             }
         }
     }

@@ -165,8 +165,7 @@ struct DecTile {
 };
 
 template <int R>
-__device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restrict__ Ku,
-                                          const bf16_t* __restrict__ Vu, int tok0, int lane)
+__device__ __forceinline__ void load_tile_k(DecTile<R>& T, const bf16_t* __restrict__ Ku, int tok0, int lane)
 {
     const bf16_t* kb = Ku + (size_t)(tok0 >> 4) * (16 * R) + lane * 8;
 #pragma unroll
@@ -179,9 +178,22 @@ __device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restric
                                        (4 * DecTile<R>::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1));
         }
     }
+}
+
+template <int R>
+__device__ __forceinline__ void load_tile_v(DecTile<R>& T, const bf16_t* __restrict__ Vu, int tok0, int lane)
+{
     const bf16_t* vb = Vu + (size_t)(tok0 >> 5) * 4096 + lane * 8;
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb) T.vf[cb] = *(const bf16x8*)(vb + cb * 512);
+}
+
+template <int R>
+__device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restrict__ Ku,
+                                          const bf16_t* __restrict__ Vu, int tok0, int lane)
+{
+    load_tile_k<R>(T, Ku, tok0, lane);
+    load_tile_v<R>(T, Vu, tok0, lane);
 }
 
 template <int R>
@@ -190,10 +202,11 @@ struct DecState {
     f32x4 O[8];
 };
 
-template <int R>
+template <int R, bool REFILL_K = false>
 __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, const bf16x8 (&qh)[DecTile<R>::NFA],
                                              const bf16x8 (&ql)[DecTile<R>::NFA], s16x4 qth, s16x4 qtl, int tok0,
-                                             int t1, int g)
+                                             int t1, int g, const bf16_t* __restrict__ Ku_next = nullptr,
+                                             int tok_next = 0, int lane = 0)
 {
     f32x4 s[2];
 #pragma unroll
@@ -209,6 +222,9 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
             s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qtl, s[tb], 0, 0, 0);
         }
     }
+    // the K~ registers of this buffer are free once the scores are issued: refill them now,
+    // a whole softmax + P.V earlier than the V part (steady-state loop only)
+    if (REFILL_K) load_tile_k<R>(T, Ku_next, tok_next, lane);
     if (tok0 + 32 > t1) {
         // last, partial tile of the split: rows past the end may hold anything (even NaN
         // patterns), so mask their scores and zero their Value slots
@@ -426,10 +442,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         // (s_waitcnt vmcnt) are exact and a wave never waits for its newest prefetch.
         int k = 0;
         for (; k + 3 < nk; k += 2) {
-            compute_tile<R>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g);
-            load_tile<R>(TA, Ku, Vu, tokA + 128 * (k + 2), lane);
-            compute_tile<R>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g);
-            load_tile<R>(TB, Ku, Vu, tokA + 128 * (k + 3), lane);
+            compute_tile<R, true>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g, Ku, tokA + 128 * (k + 2), lane);
+            load_tile_v<R>(TA, Vu, tokA + 128 * (k + 2), lane);
+            compute_tile<R, true>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g, Ku, tokA + 128 * (k + 3), lane);
+            load_tile_v<R>(TB, Vu, tokA + 128 * (k + 3), lane);
         }
         // tail: up to three tiles left (A, B, A)
         if (k < nk) {
