@@ -47,6 +47,10 @@ def lib():
         L.orc_compress_batch.argtypes = [_D, C.c_int, C.c_int64, C.c_int, _I32, _D, C.c_int, C.c_int, _D]
         L.orc_decode_batch.argtypes = [_D, _D, _D, _D, _D, _I32, C.c_int, C.c_int, C.c_int, C.c_int64,
                                        C.c_int, C.c_int, C.c_double, _D]
+        L.orc_decode_dual_head.argtypes = [_D, _D, _D, C.c_int64, _D, _D, C.c_int64, _D, _D, C.c_int, C.c_int,
+                                           C.c_double, _D]
+        L.orc_decode_dual_batch.argtypes = [_D, _D, _D, _D, _D, _D, _D, _I32, _I32, C.c_int, C.c_int, C.c_int,
+                                            C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double, _D]
         L.orc_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -221,6 +225,33 @@ def decode_batch(q, Kt, V, Rr, dmu=None, lens=None, scale=0.0):
     out = np.empty((B, Hq, d))
     lib().orc_decode_batch(_p(q), _p(Kt), _p(V), _p(Rr), _p(dmu), _p(lens, _I32), B, Hq, Hkv, cap, d, r,
                            float(scale), _p(out))
+    return out
+
+
+def decode_dual_head(q, Kt, Vvis, Kpt, Vpt, Rr, dmu=None, scale=0.0):
+    """Alg. 2 steps 1-6 for one query head: Kt [N,r], Vvis [N,d], Kpt/Vpt [M,d]."""
+    q, Kt, Vvis, Kpt, Vpt, Rr = _f64(q), _f64(Kt), _f64(Vvis), _f64(Kpt), _f64(Vpt), _f64(Rr)
+    d = q.size
+    N, r = Kt.shape if Kt.size else (0, Rr.shape[1])
+    M = Kpt.shape[0] if Kpt.size else 0
+    dmu = None if dmu is None else _f64(dmu)
+    out = np.empty(d)
+    lib().orc_decode_dual_head(_p(q), _p(Kt), _p(Vvis), N, _p(Kpt), _p(Vpt), M, _p(Rr), _p(dmu), d, r,
+                               float(scale), _p(out))
+    return out
+
+
+def decode_dual_batch(q, Kt, V, Kpt, Vpt, Rr, dmu=None, lens=None, lens_t=None, scale=0.0):
+    """decode_batch plus a prompt/text segment Kpt, Vpt [B,Hkv,cap_t,d] with lengths lens_t."""
+    q, Kt, V, Kpt, Vpt, Rr = _f64(q), _f64(Kt), _f64(V), _f64(Kpt), _f64(Vpt), _f64(Rr)
+    B, Hq, d = q.shape
+    _, Hkv, cap, r = Kt.shape
+    cap_t = Kpt.shape[2]
+    dmu = None if dmu is None else _f64(dmu)
+    lens, lens_t = _i32(lens), _i32(lens_t)
+    out = np.empty((B, Hq, d))
+    lib().orc_decode_dual_batch(_p(q), _p(Kt), _p(V), _p(Kpt), _p(Vpt), _p(Rr), _p(dmu), _p(lens, _I32),
+                                _p(lens_t, _I32), B, Hq, Hkv, cap, cap_t, d, r, float(scale), _p(out))
     return out
 
 

@@ -275,6 +275,51 @@ void orc_decode_head(const double* q, const double* Kt, const double* V,
     free(qt); free(s);
 }
 
+/* Alg. 2 in full for one query head: the visual segment is scored in the rotated
+ * basis with the mean-correction bias (steps 1-3), the prompt/text segment with
+ * its unrotated full-width Keys and no bias (step 4); the two score vectors are
+ * concatenated (step 5) and ONE softmax over all N + M tokens weights the
+ * concatenated Values [V_vis; V_pt] (step 6).  N = 0 and/or M = 0 allowed;
+ * N + M = 0 gives zeros.                                                      */
+void orc_decode_dual_head(const double* q, const double* Kt, const double* Vvis, int64_t N,
+                          const double* Kpt, const double* Vpt, int64_t M,
+                          const double* Rr, const double* dmu, int d, int r,
+                          double scale_override, double* out)
+{
+    for (int c = 0; c < d; ++c) out[c] = 0.0;
+    if (N + M <= 0) return;
+    double scale = scale_override > 0.0 ? scale_override : 1.0 / sqrt((double)d);
+    double* qt = (double*)malloc(sizeof(double) * (size_t)r);
+    double* s = (double*)malloc(sizeof(double) * (size_t)(N + M));
+    for (int j = 0; j < r; ++j) {
+        double a = 0.0;
+        for (int c = 0; c < d; ++c) a += q[c] * Rr[c * r + j];
+        qt[j] = a;
+    }
+    double b = 0.0;
+    if (dmu) for (int c = 0; c < d; ++c) b += q[c] * dmu[c];
+    for (int64_t n = 0; n < N; ++n) {
+        double a = 0.0;
+        for (int j = 0; j < r; ++j) a += qt[j] * Kt[n * r + j];
+        s[n] = (a + b) * scale;
+    }
+    for (int64_t m = 0; m < M; ++m) {
+        double a = 0.0;
+        for (int c = 0; c < d; ++c) a += q[c] * Kpt[m * d + c];
+        s[N + m] = a * scale;
+    }
+    double mx = -INFINITY;
+    for (int64_t n = 0; n < N + M; ++n) if (s[n] > mx) mx = s[n];
+    double Z = 0.0;
+    for (int64_t n = 0; n < N + M; ++n) { s[n] = exp(s[n] - mx); Z += s[n]; }
+    for (int64_t n = 0; n < N + M; ++n) {
+        double p = s[n] / Z;
+        const double* v = n < N ? Vvis + n * d : Vpt + (n - N) * d;
+        for (int c = 0; c < d; ++c) out[c] += p * v[c];
+    }
+    free(qt); free(s);
+}
+
 /* Plain full attention softmax(q K^T / sqrt(d)) V on unrotated keys (the
  * left-hand side of Eq. 1); used by the self-checks.                          */
 void orc_full_attn_head(const double* q, const double* K, const double* V,
@@ -359,6 +404,27 @@ void orc_decode_batch(const double* q, const double* Kt, const double* V,
                         Rr + kv * d * r, dmu ? dmu + kv * d : NULL,
                         lens ? lens[b] : cap, d, r, scale_override,
                         out + (size_t)u * d, NULL);
+    }
+}
+
+/* Alg. 2 in full for a batch: as orc_decode_batch plus the prompt/text segment
+ * Kpt, Vpt [B,Hkv,cap_t,d] with lengths lens_t [B] (NULL: cap_t).             */
+void orc_decode_dual_batch(const double* q, const double* Kt, const double* V,
+                           const double* Kpt, const double* Vpt,
+                           const double* Rr, const double* dmu, const int32_t* lens,
+                           const int32_t* lens_t, int B, int Hq, int Hkv, int64_t cap,
+                           int64_t cap_t, int d, int r, double scale_override, double* out)
+{
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < B * Hq; ++u) {
+        int b = u / Hq, h = u % Hq, hk = h / G;
+        size_t kv = (size_t)b * Hkv + hk;
+        orc_decode_dual_head(q + (size_t)u * d, Kt + kv * cap * r, V + kv * cap * d,
+                             lens ? lens[b] : cap, Kpt + kv * cap_t * d, Vpt + kv * cap_t * d,
+                             lens_t ? lens_t[b] : cap_t, Rr + kv * d * r,
+                             dmu ? dmu + kv * d : NULL, d, r, scale_override,
+                             out + (size_t)u * d);
     }
 }
 
