@@ -103,6 +103,22 @@ typedef struct {
     const int64_t* tok_off;        /* device [B+1]; required with tok_idx */
 } rk_rows;
 
+/* The unrotated, full-width prompt/text segment of the cache (Alg. 2 inputs
+ * K_pt [M x d] and the text rows of V; Fig. 3(b)): element (b, h, t, c) of both
+ * k and v is at data[b*stride_b + h*stride_h + t*stride_t + c], L->dtype, device
+ * memory, caller-owned.  Bases 16-byte aligned and strides multiples of 8
+ * elements.  Sequence b holds len[b] <= max_len rows (len device [B]; NULL =
+ * max_len for every sequence, rk_decode_attn_dual only); max_len is the host's
+ * upper bound of them and capacity the rows allocated per (b, h).            */
+typedef struct {
+    void* k;
+    void* v;
+    int64_t stride_b, stride_h, stride_t;
+    int32_t capacity;
+    int32_t max_len;
+    int32_t* len;
+} rk_text;
+
 /* Outputs of rk_fit_rotation (all device, fp32 unless noted). */
 typedef struct {
     float* R;            /* [B,H_kv,d,d]  column c = eigenvector of eigvals[c] (solver order) */
@@ -196,6 +212,32 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
 rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
                          const void* v_cache, const float* R_r, const float* delta_mu, float scale,
                          void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Alg. 2 in full: steps 1-6 with the prompt/text segment (App. C phase 2) --
+ * As rk_decode_attn for the visual segment; in addition the len[b] rows of
+ * `text` are scored with the unrotated query, s_pt = q . K_pt * scale (no
+ * bias), and ONE softmax runs over the concatenation [s_vis; s_pt]; out =
+ * P [V_vis; V_pt].  The bias therefore matters here: it shifts the visual
+ * scores against the text scores.  Either segment may be empty per sequence;
+ * both empty yields zeros.  Always two launches: the split-K kernel over the
+ * visual cache, then one kernel that runs the text attention and folds the
+ * visual partials (the fusion App. C describes).  Same workspace as
+ * rk_decode_attn.
+ * Errors: as rk_decode_attn, plus INVALID_ARG for a malformed `text`
+ * (NULL pointers, misaligned base or strides, max_len > capacity).            */
+rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                              const void* v_cache, const float* R_r, const float* delta_mu,
+                              const rk_text* text, float scale, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/* Append one full-width token per sequence to the text segment (the paper keeps
+ * tokens that arrive after prefill unrotated; they are the K_pt rows of Alg. 2):
+ * row len[b] of text->k / text->v receives k_new / v_new [B,H_kv,d] (L->dtype)
+ * for every KV head, then len[b] += 1 on the device.  text->len must be given.
+ * Returns RK_ERR_CAPACITY if text->max_len + 1 > text->capacity (nothing is
+ * launched); on the device a sequence already at capacity is left untouched.  */
+rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, const void* k_new,
+                         const void* v_new, void* stream);
 
 #ifdef __cplusplus
 }

@@ -27,6 +27,7 @@ EXPORTS = [
     "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
+    "rk_decode_attn_dual", "rk_append_text",
 ]
 
 
@@ -48,6 +49,11 @@ class rk_fit_out(C.Structure):
                 ("sweeps", C.c_void_p)]
 
 
+class rk_text(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64),
+                ("stride_t", C.c_int64), ("capacity", C.c_int32), ("max_len", C.c_int32), ("len", C.c_void_p)]
+
+
 class RotateKError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"rotatek status {status}: {text}")
@@ -67,6 +73,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, u32, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float, C.c_size_t
         PL, PR, PF = C.POINTER(rk_layout), C.POINTER(rk_rows), C.POINTER(rk_fit_out)
+        PT = C.POINTER(rk_text)
         L.rk_create.argtypes = [C.POINTER(vp), C.c_int]
         L.rk_destroy.argtypes = [vp]
         L.rk_status_str.argtypes = [C.c_int]
@@ -87,6 +94,8 @@ def lib():
         L.rk_compress.argtypes = [vp, PL, PR, vp, vp, PR, vp, vp, vp]
         L.rk_append.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp]
         L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+        L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
+        L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
         for name in EXPORTS:
             if name not in ("rk_status_str", "rk_last_error", "rk_fit_workspace_size", "rk_decode_workspace_size"):
                 getattr(L, name).restype = C.c_int
@@ -172,6 +181,22 @@ class FitOut:
                             ("R", "eigvals", "mask", "keep_idx", "R_r", "mu", "delta_mu", "cov", "sweeps")])
 
 
+@dataclass
+class Text:
+    """Full-width prompt/text segment: k, v tensor-likes [B, H_kv, capacity, d] sharing one set of strides."""
+    k: Any
+    v: Any
+    max_len: int
+    len: Any = None                      # device int32 [B]
+    capacity: Optional[int] = None       # rows allocated per (b, h); default: k.shape[2]
+    strides: Optional[tuple] = None      # (stride_b, stride_h, stride_t) in elements
+
+    def c(self) -> rk_text:
+        st = self.strides if self.strides is not None else tuple(self.k.stride()[:3])
+        cap = self.capacity if self.capacity is not None else int(self.k.shape[2])
+        return rk_text(_ptr(self.k), _ptr(self.v), st[0], st[1], st[2], cap, self.max_len, _ptr(self.len))
+
+
 # ---- the ABI, same names -----------------------------------------------------
 def rk_create(device: int = 0) -> int:
     h = C.c_void_p()
@@ -251,3 +276,17 @@ def rk_decode_attn(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, sca
     _check(ctx, lib().rk_decode_attn(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache), _ptr(R_r),
                                      _ptr(delta_mu), float(scale), _ptr(out), _ptr(workspace), wb,
                                      _stream(stream)))
+
+
+def rk_decode_attn_dual(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, text: Text, scale: float, out,
+                        workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    tref = C.byref(text.c()) if text is not None else None
+    _check(ctx, lib().rk_decode_attn_dual(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache),
+                                          _ptr(R_r), _ptr(delta_mu), tref, float(scale), _ptr(out),
+                                          _ptr(workspace), wb, _stream(stream)))
+
+
+def rk_append_text(ctx, layout: Layout, text: Text, k_new, v_new, stream=None) -> None:
+    tref = C.byref(text.c()) if text is not None else None
+    _check(ctx, lib().rk_append_text(ctx, C.byref(layout.c()), tref, _ptr(k_new), _ptr(v_new), _stream(stream)))

@@ -99,6 +99,21 @@ bool use_mfma_decode(const rk_ctx* ctx, const rk_layout* L)
     return !(ctx && ctx->force_generic) && decode_mfma_supported(L->dtype, L->keep);
 }
 
+rk_status check_text(rk_ctx* ctx, const rk_text* t, bool need_len)
+{
+    if (!t->k || !t->v) return fail(ctx, RK_ERR_INVALID_ARG, "text: NULL k or v");
+    if (((uintptr_t)t->k & 15) || ((uintptr_t)t->v & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "text: k and v must be 16-byte aligned");
+    if (t->stride_b < 0 || t->stride_h < 0 || t->stride_t < D || (t->stride_b % 8) || (t->stride_h % 8) ||
+        (t->stride_t % 8))
+        return fail(ctx, RK_ERR_INVALID_ARG, "text: strides must be non-negative multiples of 8 elements, stride_t >= %d", D);
+    if (t->capacity < 0 || t->max_len < 0) return fail(ctx, RK_ERR_INVALID_ARG, "text: negative capacity or max_len");
+    if (t->max_len > t->capacity)
+        return fail(ctx, RK_ERR_INVALID_ARG, "text: max_len %d exceeds capacity %d", t->max_len, t->capacity);
+    if (need_len && !t->len) return fail(ctx, RK_ERR_INVALID_ARG, "text: len is NULL");
+    return RK_OK;
+}
+
 void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tps_out)
 {
     const int G = L->n_q_heads / L->n_kv_heads;
@@ -361,9 +376,9 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
     return RK_OK;
 }
 
-rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
-                         const void* v_cache, const float* R_r, const float* delta_mu, float scale, void* out,
-                         void* workspace, size_t workspace_bytes, void* stream)
+static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                               const void* v_cache, const float* R_r, const float* delta_mu, const rk_text* text,
+                               float scale, void* out, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
     rk_status s = check_layout(ctx, L);
@@ -374,6 +389,12 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
         return fail(ctx, RK_ERR_INVALID_ARG, "decode: caches must be 16-byte aligned");
     if (L->max_seq_len > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "decode: max_seq_len %d exceeds capacity %d", L->max_seq_len, L->capacity);
+    TextDev td{};
+    if (text) {
+        s = check_text(ctx, text, false);
+        if (s != RK_OK) return s;
+        td = TextDev{text->k, text->v, text->stride_b, text->stride_h, text->stride_t, text->len, text->max_len};
+    }
     const size_t need = rk_decode_workspace_size(ctx, L);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
         return fail(ctx, RK_ERR_WORKSPACE, "decode workspace: need %zu bytes, 16-byte aligned", need);
@@ -385,9 +406,49 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
     decode_plan(ctx, L, &S, &tps);
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
     e = launch_decode(L->dtype, use_mfma_decode(ctx, L), L->batch, L->n_q_heads, L->n_kv_heads, L->capacity,
-                      L->keep, S, tps, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, sc, out, (float*)workspace,
-                      as_stream(stream));
+                      L->keep, S, tps, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, sc,
+                      out, (float*)workspace, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
+    return RK_OK;
+}
+
+rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                         const void* v_cache, const float* R_r, const float* delta_mu, float scale, void* out,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, nullptr, scale, out, workspace,
+                         workspace_bytes, stream);
+}
+
+rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                              const void* v_cache, const float* R_r, const float* delta_mu, const rk_text* text,
+                              float scale, void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!text) return fail(ctx, RK_ERR_INVALID_ARG, "decode (dual): text is NULL");
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, text, scale, out, workspace,
+                         workspace_bytes, stream);
+}
+
+rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, const void* k_new,
+                         const void* v_new, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!text) return fail(ctx, RK_ERR_INVALID_ARG, "append_text: text is NULL");
+    s = check_text(ctx, text, true);
+    if (s != RK_OK) return s;
+    if (!k_new || !v_new) return fail(ctx, RK_ERR_INVALID_ARG, "append_text: NULL pointer (k_new, v_new)");
+    if (text->max_len + 1 > text->capacity)
+        return fail(ctx, RK_ERR_CAPACITY, "append_text: %d + 1 rows exceed capacity %d", text->max_len,
+                    text->capacity);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_append_text(L->dtype, L->batch, L->n_kv_heads, text->capacity, k_new, v_new, text->k, text->v,
+                           text->stride_b, text->stride_h, text->stride_t, text->len, as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "append_text launch");
     return RK_OK;
 }
 

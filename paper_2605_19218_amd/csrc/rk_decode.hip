@@ -141,6 +141,153 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
 }
 
 // ---------------------------------------------------------------------------
+// Phase 2 of App. C in full: attention over the unrotated full-width prompt/text
+// segment (Alg. 2 step 4: s_pt = q . K_pt / sqrt(d), no bias) followed by the fold
+// of the N_s visual partials; together they realise the single softmax over the
+// concatenated scores of Alg. 2 steps 5-6.  One block of 128 threads per (b, h_q).
+// The text segment is short (tens to a few hundred tokens), so it is handled with
+// plain vector code: thread = token for the scores (each lane reads its own 256- or
+// 512-byte Key row in 16-byte pieces), thread = channel for P.V (coalesced rows).
+__device__ __forceinline__ float dot_row(const float* __restrict__ row, const float* __restrict__ qs)
+{
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < D; c += 4) {
+        const float4 kv = *(const float4*)(row + c);
+        a0 = fmaf(qs[c], kv.x, a0);
+        a1 = fmaf(qs[c + 1], kv.y, a1);
+        a2 = fmaf(qs[c + 2], kv.z, a2);
+        a3 = fmaf(qs[c + 3], kv.w, a3);
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
+__device__ __forceinline__ float dot_row(const bf16_t* __restrict__ row, const float* __restrict__ qs)
+{
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
+    for (int c = 0; c < D; c += 8) {
+        const uint4 kv = *(const uint4*)(row + c);
+        a0 = fmaf(qs[c], __uint_as_float(kv.x << 16), a0);
+        a1 = fmaf(qs[c + 1], __uint_as_float(kv.x & 0xffff0000u), a1);
+        a2 = fmaf(qs[c + 2], __uint_as_float(kv.y << 16), a2);
+        a3 = fmaf(qs[c + 3], __uint_as_float(kv.y & 0xffff0000u), a3);
+        a0 = fmaf(qs[c + 4], __uint_as_float(kv.z << 16), a0);
+        a1 = fmaf(qs[c + 5], __uint_as_float(kv.z & 0xffff0000u), a1);
+        a2 = fmaf(qs[c + 6], __uint_as_float(kv.w << 16), a2);
+        a3 = fmaf(qs[c + 7], __uint_as_float(kv.w & 0xffff0000u), a3);
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
+template <typename T>
+__global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q, TextDev text, int Hq, int Hkv,
+                                                         float scale_log2, const float* __restrict__ ws_m,
+                                                         const float* __restrict__ ws_l,
+                                                         const float* __restrict__ ws_acc, int S,
+                                                         T* __restrict__ out)
+{
+    const size_t row = blockIdx.x;         // b * Hq + hq
+    const int b = (int)(row / Hq), hq = (int)(row % Hq), hk = hq / (Hq / Hkv);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) float qs[D];
+    __shared__ float ps[128], red[4];
+
+    // visual partials of the first chunk: issued before the text loop so their latency hides behind it
+    const float* m = ws_m + row * S;
+    const float* l = ws_l + row * S;
+    const float* a = ws_acc + row * S * D + tid;
+
+    qs[tid] = ld_elem(q + row * D + tid);
+    __syncthreads();
+
+    float Mx = NEG_INF, den = 0.f, num = 0.f;
+    const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
+    const T* Kt = (const T*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh;
+    const T* Vt = (const T*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh;
+    for (int base = 0; base < Mt; base += 128) {
+        const int tok = base + tid;
+        const bool valid = tok < Mt;
+        const float s = valid ? dot_row(Kt + (int64_t)tok * text.st, qs) * scale_log2 : NEG_INF;
+        float mt = wave_max(s);
+        if (lane == 0) red[wave] = mt;
+        __syncthreads();
+        const float m_new = fmaxf(Mx, fmaxf(red[0], red[1]));     // finite: the chunk holds >= 1 token
+        const float p = valid ? exp2f(s - m_new) : 0.f;
+        ps[tid] = p;
+        float lsum = wave_sum(p);
+        if (lane == 0) red[2 + wave] = lsum;
+        __syncthreads();
+        const float alpha = exp2f(Mx - m_new);                     // 0 on the first chunk
+        den = den * alpha + (red[2] + red[3]);
+        num *= alpha;
+        const int nv = min(128, Mt - base);
+        const T* vrow = Vt + (int64_t)base * text.st + tid;
+        int t = 0;
+        for (; t + 8 <= nv; t += 8) {
+            float vv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) vv[k] = ld_elem(vrow + (int64_t)(t + k) * text.st);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) num = fmaf(ps[t + k], vv[k], num);
+        }
+        for (; t < nv; ++t) num = fmaf(ps[t], ld_elem(vrow + (int64_t)t * text.st), num);
+        Mx = m_new;
+        __syncthreads();
+    }
+
+    // fold the visual partials (same arithmetic as decode_merge, starting from the text state)
+    for (int i0 = 0; i0 < S; i0 += 16) {
+        float av[16], mv[16], lv[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const bool in = i0 + k < S;
+            av[k] = in ? a[(size_t)(i0 + k) * D] : 0.f;
+            mv[k] = in ? m[i0 + k] : NEG_INF;
+            lv[k] = in ? l[i0 + k] : 0.f;
+        }
+        float Mc = Mx;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) Mc = fmaxf(Mc, mv[k]);
+        if (Mc > NEG_INF) {
+            const float resc = exp2f(Mx - Mc);
+            den *= resc;
+            num *= resc;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                float w = exp2f(mv[k] - Mc);
+                den = fmaf(lv[k], w, den);
+                num = fmaf(av[k], w, num);
+            }
+            Mx = Mc;
+        }
+    }
+    const float o = (Mx > NEG_INF) ? num / den : 0.f;
+    st_elem(out + row * D + tid, o);
+}
+
+// One token per sequence appended to the full-width text segment (the paper keeps
+// tokens that arrive after prefill unrotated, Alg. 2 input K_pt); block = batch item.
+template <typename T>
+__global__ __launch_bounds__(128) void append_text_rows(const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                                        T* __restrict__ kt, T* __restrict__ vt, int64_t sb,
+                                                        int64_t sh, int64_t st, int Hkv, int capacity,
+                                                        int32_t* __restrict__ len)
+{
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int pos = len[b];
+    if (pos < 0 || pos >= capacity) return;              // uniform: full (or corrupt) sequences are left alone
+    for (int h = 0; h < Hkv; ++h) {
+        const size_t src = ((size_t)b * Hkv + h) * D + tid;
+        const int64_t dst = (int64_t)b * sb + (int64_t)h * sh + (int64_t)pos * st + tid;
+        kt[dst] = k_new[src];
+        vt[dst] = v_new[src];
+    }
+    __syncthreads();                                     // every thread has read len[b] before it moves
+    if (tid == 0) len[b] = pos + 1;
+}
+
+// ---------------------------------------------------------------------------
 // MFMA split-K kernel (bf16 cache, r a multiple of 16).  256 threads = 4 waves;
 // grid (split, H_kv * head groups of 16, B).  Each wave walks its own 32-token
 // tiles (tile index = wave, wave + 4, ...) with a private online-softmax state and
@@ -296,6 +443,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     __shared__ float sdm[D];
     __shared__ float sm_m[4][16], sm_l[4][16];
 
+    const bool direct = out != nullptr;     // the only split of a single-path call writes the result itself
     const int G = Hq / Hkv;
     const int ngrp = (G + 15) >> 4;
     const int split = blockIdx.x, b = blockIdx.z;
@@ -496,12 +644,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
                 if (hh < Gc) {
                     const size_t row = (size_t)b * Hq + h0 + hh;
                     const int c = 16 * cb + n;
-                    if (S == 1) out[row * D + c] = f32_to_bf16(acc[ii] / lh[ii]);
+                    if (direct) out[row * D + c] = f32_to_bf16(acc[ii] / lh[ii]);
                     else ws_acc[(row * S + split) * D + c] = acc[ii];
                 }
             }
         }
-        if (S > 1 && wave == 0 && n == 0) {        // lanes (g, 0): m and l of heads 4g..4g+3
+        if (!direct && wave == 0 && n == 0) {        // lanes (g, 0): m and l of heads 4g..4g+3
 #pragma unroll
             for (int ii = 0; ii < 4; ++ii) {
                 const int hh = 4 * g + ii;
@@ -519,7 +667,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     for (int idx = tid; idx < Gc * D; idx += 256) {
         int hh = idx >> 7, c = idx & 127;
         const size_t row = (size_t)b * Hq + h0 + hh;
-        if (S == 1) {
+        if (out != nullptr) {
             out[row * D + c] = f32_to_bf16(0.f);
         } else {
             const size_t pidx = row * S + split;
@@ -543,13 +691,16 @@ static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, con
 
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
-                         const int32_t* seq_len, float scale, void* out, float* ws, hipStream_t st)
+                         const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
+                         hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
     float* ws_m = ws;
     float* ws_l = ws_m + rows * S;
     float* ws_acc = ws_l + rows * S;
     const float sl2 = scale * 1.4426950408889634f;    // scores in the log2 domain
+    const bool direct = S == 1 && text == nullptr;    // a single split of a single-path call writes `out` itself
+    hipError_t e;
     if (mfma && decode_mfma_supported(dtype, r)) {
         const int G = Hq / Hkv;
         dim3 grid(S, Hkv * ((G + 15) / 16), B);
@@ -557,35 +708,55 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
         launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tps, sl2, ws_m, ws_l, \
-                                 ws_acc, S, (bf16_t*)out);                                                 \
+                                 ws_acc, S, direct ? (bf16_t*)out : nullptr);                              \
         break;
         switch (r) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
             default: return hipErrorInvalidValue;
         }
 #undef RK_CASE
-        hipError_t e0 = hipGetLastError();
-        if (e0 != hipSuccess || S == 1) return e0;       // a single split writes `out` itself
-        hipLaunchKernelGGL(decode_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
-                           (bf16_t*)out);
-        return hipGetLastError();
+        e = hipGetLastError();
+        if (e != hipSuccess || direct) return e;
+    } else {
+        dim3 grid(S, Hq, B);
+        if (dtype == 0)
+            hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q,
+                               (const float*)Kp, (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
+                               ws_m, ws_l, ws_acc, S);
+        else
+            hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
+                               (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
+                               ws_m, ws_l, ws_acc, S);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    dim3 grid(S, Hq, B);
-    if (dtype == 0)
-        hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q, (const float*)Kp,
-                           (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2, ws_m, ws_l, ws_acc, S);
-    else
-        hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
-                           (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
-                           ws_m, ws_l, ws_acc, S);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (dtype == 0)
+    if (text) {
+        if (dtype == 0)
+            hipLaunchKernelGGL(decode_text_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, (const float*)q,
+                               *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (float*)out);
+        else
+            hipLaunchKernelGGL(decode_text_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st,
+                               (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out);
+    } else if (dtype == 0) {
         hipLaunchKernelGGL(decode_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
                            (float*)out);
-    else
+    } else {
         hipLaunchKernelGGL(decode_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
                            (bf16_t*)out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,
+                              void* kt, void* vt, int64_t sb, int64_t sh, int64_t st_, int32_t* len,
+                              hipStream_t st)
+{
+    if (dtype == 0)
+        hipLaunchKernelGGL(append_text_rows<float>, dim3(B), dim3(128), 0, st, (const float*)k_new,
+                           (const float*)v_new, (float*)kt, (float*)vt, sb, sh, st_, Hkv, capacity, len);
+    else
+        hipLaunchKernelGGL(append_text_rows<bf16_t>, dim3(B), dim3(128), 0, st, (const bf16_t*)k_new,
+                           (const bf16_t*)v_new, (bf16_t*)kt, (bf16_t*)vt, sb, sh, st_, Hkv, capacity, len);
     return hipGetLastError();
 }
 

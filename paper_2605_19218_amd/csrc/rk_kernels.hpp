@@ -35,8 +35,21 @@ hipError_t launch_unpack(int dtype, int U, int cap, int r, const void* Kp, const
 // ---- rk_decode.hip ---------------------------------------------------------
 // Partials: m [B,Hq,S], l [B,Hq,S], acc [B,Hq,S,d]; m is in the log2 domain.
 bool decode_mfma_supported(int dtype, int r);
+// Unrotated full-width prompt/text segment (Alg. 2 input K_pt and its Value rows).
+struct TextDev {
+    const void* k;
+    const void* v;
+    int64_t sb, sh, st;      // element strides of [B, H_kv, token, d], shared by k and v
+    const int32_t* len;      // device [B] or null (= max_len)
+    int max_len;
+};
+// text == nullptr: visual segment only; otherwise the text segment joins the softmax in the merge kernel
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
-                         const int32_t* seq_len, float scale, void* out, float* ws, hipStream_t st);
+                         const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
+                         hipStream_t st);
+hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,
+                              void* kt, void* vt, int64_t sb, int64_t sh, int64_t st_, int32_t* len,
+                              hipStream_t st);
 
 }  // namespace rk

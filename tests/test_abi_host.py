@@ -143,6 +143,35 @@ def test_decode_plan_and_options(ctx):
     assert rk.rk_decode_plan(ctx, layout(max_seq_len=0))[0] == 1
 
 
+def text(**kw):
+    base = dict(k=PTR, v=PTR, max_len=64, len=PTR, capacity=64, strides=(2 * 64 * 128, 64 * 128, 128))
+    base.update(kw)
+    return rk.Text(**base)
+
+
+def test_dual_decode_and_text_append_validation(ctx):
+    lay = layout()
+    ws = rk.rk_decode_workspace_size(ctx, lay)
+    dec = lambda t, **kw: status_of(rk.rk_decode_attn_dual, ctx, kw.get("lay", lay), PTR, PTR, PTR, PTR, PTR, t, 0.0,
+                                    PTR, PTR, workspace_bytes=kw.get("ws", ws))
+    assert dec(text()) == rk.RK_ERR_NO_DEVICE
+    assert dec(text(len=None)) == rk.RK_ERR_NO_DEVICE            # NULL len = max_len rows everywhere
+    assert dec(None) == rk.RK_ERR_INVALID_ARG
+    assert dec(text(k=None)) == rk.RK_ERR_INVALID_ARG
+    assert dec(text(v=PTR + 2)) == rk.RK_ERR_INVALID_ARG          # misaligned base
+    assert dec(text(strides=(2 * 64 * 128, 64 * 128, 100))) == rk.RK_ERR_INVALID_ARG   # rows overlap / misaligned
+    assert dec(text(strides=(2 * 64 * 132, 64 * 132, 132))) == rk.RK_ERR_INVALID_ARG   # not a multiple of 8
+    assert dec(text(max_len=65)) == rk.RK_ERR_INVALID_ARG
+    assert dec(text(), ws=ws - 1) == rk.RK_ERR_WORKSPACE
+    assert dec(text(), lay=layout(max_seq_len=2000)) == rk.RK_ERR_CAPACITY
+    app = lambda t, k=PTR, v=PTR: status_of(rk.rk_append_text, ctx, lay, t, k, v)
+    assert app(text(max_len=63)) == rk.RK_ERR_NO_DEVICE
+    assert app(text()) == rk.RK_ERR_CAPACITY
+    assert app(text(max_len=63, len=None)) == rk.RK_ERR_INVALID_ARG
+    assert app(text(max_len=63), k=None) == rk.RK_ERR_INVALID_ARG
+    assert app(None) == rk.RK_ERR_INVALID_ARG
+
+
 def test_product_does_not_import_oracle():
     """The product path must not route through the CPU oracle."""
     pkg = os.path.join(ROOT, "paper_2605_19218_amd")
