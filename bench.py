@@ -205,6 +205,35 @@ def main():
             del stt
             torch.cuda.empty_cache()
 
+    # ---- dual-path decode (Alg. 2 steps 4-5): the same cache plus a 64-token full-width text segment ----
+    dual = None
+    if not args.no_sweep:
+        M = 64
+        tcfg = dict(cfg, id=cfg["id"] + 500, L=M)
+        tl = make_layer(tcfg, 0)
+        text = rk.Text(to_bf16(tl["K"]), to_bf16(tl["V"]), M,
+                       torch.full((B,), M, device=dev, dtype=torch.int32), capacity=M)
+        for i in range(NL):
+            do_compress(r_main, state[i], layers[i])       # reset lengths to L
+
+        def do_dual(st, ly):
+            _, dl = layouts(r_main, st)
+            rk.rk_decode_attn_dual(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], text, 0.0,
+                                   st["out"], dec_ws)
+        for i in range(args.warmup):
+            do_dual(state[i % NL], layers[i % NL])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            do_dual(state[i % NL], layers[i % NL])
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        dbytes = decode_bytes(r_main, L) + B * Hkv * M * 2 * D * 2
+        dual = dict(text_tokens=M, us_per_step=us, GBps=dbytes / (us * 1e-6) / 1e9,
+                    single_path_us=sweep[str(r_main)]["us_per_step"])
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, device=dev, dtype=torch.uint8).random_(0, 255)
         dst = torch.empty_like(src)
@@ -262,6 +291,7 @@ def main():
         "compress_GBps": comp_gbps,
         "stages_us": stage_us,
         "decode_only_sweep": sweep,
+        "dual_path_decode": dual,
         "roofline": {"bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": committed_traffic("decode_split_mfma<64>"),
                      "kernel": "decode_split_mfma<64> + decode_merge (one rk_decode_attn call; the duration is the "

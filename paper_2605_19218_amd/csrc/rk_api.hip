@@ -393,6 +393,7 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     if (text) {
         s = check_text(ctx, text, false);
         if (s != RK_OK) return s;
+        if ((uintptr_t)q & 15) return fail(ctx, RK_ERR_INVALID_ARG, "decode (dual): q must be 16-byte aligned");
         td = TextDev{text->k, text->v, text->stride_b, text->stride_h, text->stride_t, text->len, text->max_len};
     }
     const size_t need = rk_decode_workspace_size(ctx, L);

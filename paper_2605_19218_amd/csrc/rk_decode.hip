@@ -148,38 +148,42 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
 // The text segment is short (tens to a few hundred tokens), so it is handled with
 // plain vector code: thread = token for the scores (each lane reads its own 256- or
 // 512-byte Key row in 16-byte pieces), thread = channel for P.V (coalesced rows).
-__device__ __forceinline__ float dot_row(const float* __restrict__ row, const float* __restrict__ qs)
+__device__ __forceinline__ void load_partials(const float* __restrict__ m, const float* __restrict__ l,
+                                              const float* __restrict__ a, int i0, int S, float (&mv)[16],
+                                              float (&lv)[16], float (&av)[16])
 {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < D; c += 4) {
-        const float4 kv = *(const float4*)(row + c);
-        a0 = fmaf(qs[c], kv.x, a0);
-        a1 = fmaf(qs[c + 1], kv.y, a1);
-        a2 = fmaf(qs[c + 2], kv.z, a2);
-        a3 = fmaf(qs[c + 3], kv.w, a3);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const bool in = i0 + k < S;
+        av[k] = in ? a[(size_t)(i0 + k) * D] : 0.f;
+        mv[k] = in ? m[i0 + k] : NEG_INF;
+        lv[k] = in ? l[i0 + k] : 0.f;
     }
-    return (a0 + a1) + (a2 + a3);
 }
 
-__device__ __forceinline__ float dot_row(const bf16_t* __restrict__ row, const float* __restrict__ qs)
+// 16 bytes of storage -> fp32 values (8 bf16 or 4 fp32)
+__device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[8], const bf16_t*)
 {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 4
-    for (int c = 0; c < D; c += 8) {
-        const uint4 kv = *(const uint4*)(row + c);
-        a0 = fmaf(qs[c], __uint_as_float(kv.x << 16), a0);
-        a1 = fmaf(qs[c + 1], __uint_as_float(kv.x & 0xffff0000u), a1);
-        a2 = fmaf(qs[c + 2], __uint_as_float(kv.y << 16), a2);
-        a3 = fmaf(qs[c + 3], __uint_as_float(kv.y & 0xffff0000u), a3);
-        a0 = fmaf(qs[c + 4], __uint_as_float(kv.z << 16), a0);
-        a1 = fmaf(qs[c + 5], __uint_as_float(kv.z & 0xffff0000u), a1);
-        a2 = fmaf(qs[c + 6], __uint_as_float(kv.w << 16), a2);
-        a3 = fmaf(qs[c + 7], __uint_as_float(kv.w & 0xffff0000u), a3);
-    }
-    return (a0 + a1) + (a2 + a3);
+    f[0] = __uint_as_float(raw.x << 16); f[1] = __uint_as_float(raw.x & 0xffff0000u);
+    f[2] = __uint_as_float(raw.y << 16); f[3] = __uint_as_float(raw.y & 0xffff0000u);
+    f[4] = __uint_as_float(raw.z << 16); f[5] = __uint_as_float(raw.z & 0xffff0000u);
+    f[6] = __uint_as_float(raw.w << 16); f[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+__device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[4], const float*)
+{
+    f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y);
+    f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
 }
 
+// Register mappings (EPV = elements per 16-byte piece: 8 for bf16, 4 for fp32):
+//   scores: thread (token tid / 2, half tid % 2) holds half a Key row and the matching
+//           half of q; the two halves meet in one lane exchange;
+//   P.V   : thread (channel group tid % CG, token group tid / CG) holds the 16-byte
+//           piece of every TG-th Value row of the pass; the TG partial sums meet in
+//           LDS once, after the last pass.
+// All loads of a pass (and, before the first pass, q and the first 16 visual
+// partials) are issued before anything waits, so a typical 64-token text segment
+// costs one memory round trip on top of the fold.
 template <typename T>
 __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q, TextDev text, int Hq, int Hkv,
                                                          float scale_log2, const float* __restrict__ ws_m,
@@ -187,65 +191,100 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
                                                          const float* __restrict__ ws_acc, int S,
                                                          T* __restrict__ out)
 {
-    const size_t row = blockIdx.x;         // b * Hq + hq
+    constexpr int EPV = 16 / (int)sizeof(T);
+    constexpr int CG = D / EPV;                 // channel groups: 16 or 32
+    constexpr int TG = 128 / CG;                // token groups: 8 or 4
+    constexpr int CHUNK = 64;                   // text tokens per pass
+    constexpr int NV = CHUNK / TG;              // Value pieces per thread and pass
+    constexpr int NKQ = (D / 2) / EPV;          // pieces of half a Key row
+
+    const size_t row = blockIdx.x;              // b * Hq + hq
     const int b = (int)(row / Hq), hq = (int)(row % Hq), hk = hq / (Hq / Hkv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ __attribute__((aligned(16))) float qs[D];
-    __shared__ float ps[128], red[4];
+    const int ts = tid >> 1, half = tid & 1;
+    const int cg = tid % CG, tg = tid / CG;
+    __shared__ float ps[CHUNK], red[4];
+    __shared__ float part[TG][D];
 
-    // visual partials of the first chunk: issued before the text loop so their latency hides behind it
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
     const float* a = ws_acc + row * S * D + tid;
-
-    qs[tid] = ld_elem(q + row * D + tid);
-    __syncthreads();
-
-    float Mx = NEG_INF, den = 0.f, num = 0.f;
     const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
     const T* Kt = (const T*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh;
     const T* Vt = (const T*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh;
-    for (int base = 0; base < Mt; base += 128) {
-        const int tok = base + tid;
+
+    uint4 qraw[NKQ];
+#pragma unroll
+    for (int i = 0; i < NKQ; ++i) qraw[i] = *(const uint4*)(q + row * D + half * (D / 2) + i * EPV);
+
+    float av[16], mv[16], lv[16];
+    load_partials(m, l, a, 0, S, mv, lv, av);   // in flight during the text passes
+
+    float Mx = NEG_INF, den = 0.f;
+    float acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+
+    for (int base = 0; base < Mt; base += CHUNK) {
+        uint4 kraw[NKQ], vraw[NV];
+        const int tok = base + ts;
         const bool valid = tok < Mt;
-        const float s = valid ? dot_row(Kt + (int64_t)tok * text.st, qs) * scale_log2 : NEG_INF;
+        const T* krow = Kt + (int64_t)min(tok, Mt - 1) * text.st + half * (D / 2);
+#pragma unroll
+        for (int i = 0; i < NKQ; ++i) kraw[i] = *(const uint4*)(krow + i * EPV);
+#pragma unroll
+        for (int k = 0; k < NV; ++k)      // rows past the end are clamped; their weight is 0
+            vraw[k] = *(const uint4*)(Vt + (int64_t)min(base + tg + TG * k, Mt - 1) * text.st + cg * EPV);
+
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NKQ; ++i) {
+            float qf[EPV], kf[EPV];
+            unpack16(qraw[i], qf, (const T*)nullptr);
+            unpack16(kraw[i], kf, (const T*)nullptr);
+#pragma unroll
+            for (int e = 0; e < EPV; e += 2) {
+                s0 = fmaf(qf[e], kf[e], s0);
+                s1 = fmaf(qf[e + 1], kf[e + 1], s1);
+            }
+        }
+        float s = s0 + s1;
+        s += __shfl_xor(s, 1);
+        s = valid ? s * scale_log2 : NEG_INF;
         float mt = wave_max(s);
         if (lane == 0) red[wave] = mt;
         __syncthreads();
-        const float m_new = fmaxf(Mx, fmaxf(red[0], red[1]));     // finite: the chunk holds >= 1 token
+        const float m_new = fmaxf(Mx, fmaxf(red[0], red[1]));     // finite: the pass holds >= 1 token
         const float p = valid ? exp2f(s - m_new) : 0.f;
-        ps[tid] = p;
-        float lsum = wave_sum(p);
+        if (half == 0) ps[ts] = p;
+        float lsum = wave_sum(half == 0 ? p : 0.f);
         if (lane == 0) red[2 + wave] = lsum;
         __syncthreads();
-        const float alpha = exp2f(Mx - m_new);                     // 0 on the first chunk
+        const float alpha = exp2f(Mx - m_new);                     // 0 on the first pass
         den = den * alpha + (red[2] + red[3]);
-        num *= alpha;
-        const int nv = min(128, Mt - base);
-        const T* vrow = Vt + (int64_t)base * text.st + tid;
-        int t = 0;
-        for (; t + 8 <= nv; t += 8) {
-            float vv[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) vv[k] = ld_elem(vrow + (int64_t)(t + k) * text.st);
+        for (int e = 0; e < EPV; ++e) acc[e] *= alpha;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) num = fmaf(ps[t + k], vv[k], num);
+        for (int k = 0; k < NV; ++k) {
+            const float w = ps[tg + TG * k];
+            float vf[EPV];
+            unpack16(vraw[k], vf, (const T*)nullptr);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(w, vf[e], acc[e]);
         }
-        for (; t < nv; ++t) num = fmaf(ps[t], ld_elem(vrow + (int64_t)t * text.st), num);
         Mx = m_new;
-        __syncthreads();
+        __syncthreads();                                           // ps and red are rewritten by the next pass
     }
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) part[tg][cg * EPV + e] = acc[e];
+    __syncthreads();
+    float num = 0.f;
+#pragma unroll
+    for (int k = 0; k < TG; ++k) num += part[k][tid];
 
     // fold the visual partials (same arithmetic as decode_merge, starting from the text state)
     for (int i0 = 0; i0 < S; i0 += 16) {
-        float av[16], mv[16], lv[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const bool in = i0 + k < S;
-            av[k] = in ? a[(size_t)(i0 + k) * D] : 0.f;
-            mv[k] = in ? m[i0 + k] : NEG_INF;
-            lv[k] = in ? l[i0 + k] : 0.f;
-        }
+        if (i0 > 0) load_partials(m, l, a, i0, S, mv, lv, av);
         float Mc = Mx;
 #pragma unroll
         for (int k = 0; k < 16; ++k) Mc = fmaxf(Mc, mv[k]);
