@@ -51,6 +51,8 @@ def lib():
                                            C.c_double, _D]
         L.orc_decode_dual_batch.argtypes = [_D, _D, _D, _D, _D, _D, _D, _I32, _I32, C.c_int, C.c_int, C.c_int,
                                             C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double, _D]
+        L.orc_subspace_iter.argtypes = [_D, C.c_int, C.c_int, _D, C.c_int, C.c_double, _D]
+        L.orc_subspace_iter.restype = C.c_int
         L.orc_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -183,6 +185,26 @@ def fit(K, r, sigma=None, center=True, tok=None):
     Rr = gather_rotation(R, keep)
     dmu = delta_mu(mu, Rr)
     return dict(mu=mu, C=Cm, Cq=Cq, R=R, lam=lam, mask=mask, keep_idx=keep, Rr=Rr, dmu=dmu, sweeps=sw)
+
+
+def subspace_iter(Cq, V0, T=5, eps=1e-6):
+    """Alg. 1 steps 6-13: T rounds of V <- Cq V followed by the shifted Cholesky-QR.  Returns V [d,k]."""
+    Cq, V0 = _f64(Cq), _f64(V0)
+    d, k = V0.shape
+    V = np.empty((d, k))
+    st = lib().orc_subspace_iter(_p(Cq), d, k, _p(V0), int(T), float(eps), _p(V))
+    if st != 0:
+        raise RuntimeError(f"oracle Cholesky met a non-positive pivot in iteration {st - 1}")
+    return V
+
+
+def fit_subspace(K, V0, T=5, eps=1e-6, sigma=None, center=True, tok=None):
+    """Alg. 1 for one head with the subspace iteration as the solver (the paper's default).
+    Returns dict(mu, C, Cq, Rr, dmu); Rr = V^(T) [d,k]."""
+    mu, Cm = mean_scatter(K, tok=tok, center=center)
+    Cq = weight(Cm, sigma)
+    Rr = subspace_iter(Cq, V0, T, eps)
+    return dict(mu=mu, C=Cm, Cq=Cq, Rr=Rr, dmu=delta_mu(mu, Rr))
 
 
 # --------------------------------------------------------------------------

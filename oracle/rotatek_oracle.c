@@ -235,6 +235,62 @@ void orc_compress(const double* K, int64_t n, int d, const int32_t* tok,
 }
 
 /* ------------------------------------------------------------------------ */
+/* Alg. 1 steps 6-13 / App. E: subspace iteration with shifted Cholesky-QR.
+ * V [d,k] starts as V0 (the caller's N(0,1) draw); T times:
+ *   V <- Cq V;  G <- V^T V;  rho <- eps * tr(G) / k;  L <- chol(G + rho I)
+ *   (lower triangular, L L^T = G + rho I);  V <- V L^{-T}.
+ * The Cholesky factor is the textbook one (row by row); V L^{-T} is a forward
+ * substitution per row of V: x L^T = v, i.e. x_j = (v_j - sum_{m<j} x_m L[j][m]) / L[j][j].
+ * Returns 0, or t+1 if iteration t met a non-positive pivot (V is then left as
+ * it was before that iteration's orthonormalisation).                          */
+int orc_subspace_iter(const double* Cq, int d, int k, const double* V0, int T, double eps, double* V)
+{
+    double* W = (double*)malloc(sizeof(double) * (size_t)d * k);
+    double* G = (double*)malloc(sizeof(double) * (size_t)k * k);
+    double* L = (double*)calloc((size_t)k * k, sizeof(double));
+    int status = 0;
+    for (int i = 0; i < d * k; ++i) V[i] = V0[i];
+    for (int t = 0; t < T && status == 0; ++t) {
+        for (int i = 0; i < d; ++i)
+            for (int j = 0; j < k; ++j) {
+                double a = 0.0;
+                for (int m = 0; m < d; ++m) a += Cq[i * d + m] * V[m * k + j];
+                W[i * k + j] = a;
+            }
+        double tr = 0.0;
+        for (int a = 0; a < k; ++a)
+            for (int b = 0; b < k; ++b) {
+                double g = 0.0;
+                for (int i = 0; i < d; ++i) g += W[i * k + a] * W[i * k + b];
+                G[a * k + b] = g;
+                if (a == b) tr += g;
+            }
+        double rho = eps * tr / (double)k;
+        for (int a = 0; a < k; ++a) G[a * k + a] += rho;
+        for (int a = 0; a < k && status == 0; ++a)
+            for (int b = 0; b <= a; ++b) {
+                double sum = G[a * k + b];
+                for (int m = 0; m < b; ++m) sum -= L[a * k + m] * L[b * k + m];
+                if (a == b) {
+                    if (!(sum > 0.0)) { status = t + 1; break; }
+                    L[a * k + a] = sqrt(sum);
+                } else {
+                    L[a * k + b] = sum / L[b * k + b];
+                }
+            }
+        if (status) break;
+        for (int i = 0; i < d; ++i)
+            for (int j = 0; j < k; ++j) {
+                double x = W[i * k + j];
+                for (int m = 0; m < j; ++m) x -= V[i * k + m] * L[j * k + m];
+                V[i * k + j] = x / L[j * k + j];
+            }
+    }
+    free(W); free(G); free(L);
+    return status;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Alg. 2 steps 1-3 and 6 for one query head over the packed cache:
  * q~ = q R_k; b = q . delta_mu (0 if dmu NULL); s_n = (q~ . K~_n + b) * scale
  * with scale = 1/sqrt(d) (the ORIGINAL head dim) unless scale_override > 0;
