@@ -170,6 +170,29 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys,
                           const float* sigma, uint32_t flags, const rk_fit_out* out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Parameters of the subspace solver (Alg. 1 inputs T and epsilon, and the draw of step 6). */
+typedef struct {
+    const float* v0;      /* device [B,H_kv,d,keep] fp32: the start basis V^(0), i.i.d. N(0,1), drawn by the caller */
+    int32_t iterations;   /* T >= 1 (the paper uses 5)                                                             */
+    double ridge;         /* epsilon >= 0 of the trace-scaled ridge rho = epsilon tr(G) / k                         */
+} rk_subspace;
+
+/* ---- Alg. 1 with the Cholesky-based subspace iteration as the solver (steps 1-13, 16; App. E)
+ * mu and the scatter as in rk_fit_rotation (same rows, sigma and flags), then T
+ * rounds of V <- C_q V, G = V^T V, L = chol(G + rho I), V <- V L^{-T}, all in one
+ * launch and in fp64.  Outputs (device, fp32): R_r [B,H_kv,d,keep] = V^(T) (a basis
+ * of the leading subspace, orthonormal up to the ridge, NOT eigenvectors one by
+ * one: there are no eigenvalues, mask or keep_idx on this route); mu, delta_mu
+ * [B,H_kv,d]; optionally cov [B,H_kv,d,d] and status [B,H_kv] (int32: 0, or t+1 if
+ * iteration t met a non-positive Cholesky pivot, in which case that head's R_r and
+ * delta_mu are undefined).  keep <= 104 (the basis and the Gram matrix stay in LDS
+ * as doubles); larger keep: RK_ERR_UNSUPPORTED, use rk_fit_rotation.  Workspace as
+ * rk_fit_rotation.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.          */
+rk_status rk_fit_subspace(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* sigma,
+                          uint32_t flags, const rk_subspace* solver, float* R_r, float* mu,
+                          float* delta_mu, float* cov, int32_t* status, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
 /* R_r[:, j] = R[:, keep_idx[j]] for every (b, h_kv): re-derives the d x r form
  * the kernels read from the canonical (R, keep_idx) state.                    */
 rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R,

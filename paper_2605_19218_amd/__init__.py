@@ -27,7 +27,7 @@ EXPORTS = [
     "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
-    "rk_decode_attn_dual", "rk_append_text",
+    "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace",
 ]
 
 
@@ -52,6 +52,10 @@ class rk_fit_out(C.Structure):
 class rk_text(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64),
                 ("stride_t", C.c_int64), ("capacity", C.c_int32), ("max_len", C.c_int32), ("len", C.c_void_p)]
+
+
+class rk_subspace(C.Structure):
+    _fields_ = [("v0", C.c_void_p), ("iterations", C.c_int32), ("ridge", C.c_double)]
 
 
 class RotateKError(RuntimeError):
@@ -96,6 +100,7 @@ def lib():
         L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
         L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
         L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
+        L.rk_fit_subspace.argtypes = [vp, PL, PR, vp, u32, C.POINTER(rk_subspace), vp, vp, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS:
             if name not in ("rk_status_str", "rk_last_error", "rk_fit_workspace_size", "rk_decode_workspace_size"):
                 getattr(L, name).restype = C.c_int
@@ -290,3 +295,13 @@ def rk_decode_attn_dual(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu
 def rk_append_text(ctx, layout: Layout, text: Text, k_new, v_new, stream=None) -> None:
     tref = C.byref(text.c()) if text is not None else None
     _check(ctx, lib().rk_append_text(ctx, C.byref(layout.c()), tref, _ptr(k_new), _ptr(v_new), _stream(stream)))
+
+
+def rk_fit_subspace(ctx, layout: Layout, keys: Rows, sigma, flags: int, v0, iterations: int, ridge: float, R_r, mu,
+                    delta_mu, workspace, cov=None, status=None, stream=None,
+                    workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    sv = rk_subspace(_ptr(v0), int(iterations), float(ridge))
+    _check(ctx, lib().rk_fit_subspace(ctx, C.byref(layout.c()), C.byref(keys.c()), _ptr(sigma), flags, C.byref(sv),
+                                      _ptr(R_r), _ptr(mu), _ptr(delta_mu), _ptr(cov), _ptr(status),
+                                      _ptr(workspace), wb, _stream(stream)))

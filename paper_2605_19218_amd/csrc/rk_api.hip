@@ -305,6 +305,51 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     return RK_OK;
 }
 
+rk_status rk_fit_subspace(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* sigma, uint32_t flags,
+                          const rk_subspace* solver, float* R_r, float* mu, float* delta_mu, float* cov_out,
+                          int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    s = check_rows(ctx, L, keys, "keys");
+    if (s != RK_OK) return s;
+    if (!solver || !solver->v0) return fail(ctx, RK_ERR_INVALID_ARG, "fit_subspace: solver or its start basis is NULL");
+    if (solver->iterations < 1 || !(solver->ridge >= 0.0))
+        return fail(ctx, RK_ERR_INVALID_ARG, "fit_subspace: iterations must be >= 1 and ridge >= 0");
+    if (!R_r || !mu || !delta_mu) return fail(ctx, RK_ERR_INVALID_ARG, "fit_subspace: a required output is NULL");
+    if (flags & ~(uint32_t)RK_FIT_CENTER) return fail(ctx, RK_ERR_INVALID_ARG, "unknown fit flags 0x%x", flags);
+    if (L->keep > subspace_max_keep())
+        return fail(ctx, RK_ERR_UNSUPPORTED, "fit_subspace: keep %d exceeds %d; use rk_fit_rotation", L->keep,
+                    subspace_max_keep());
+    const FitWs w = fit_ws(L, keys->n_tokens);
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))
+        return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    const int B = L->batch, Hkv = L->n_kv_heads, U = B * Hkv;
+    const int ct = cov_chunk_tokens(L->dtype, !ctx->force_generic);
+    int nc = (keys->n_tokens + ct - 1) / ct;
+    if (nc < 1) nc = 1;
+    char* ws = (char*)workspace;
+    float* part_S = (float*)(ws + w.part_S);
+    float* part_sum = (float*)(ws + w.part_sum);
+    float* cov = cov_out ? cov_out : (float*)(ws + w.cov);
+    const RowsDev rows = to_dev(keys);
+    hipStream_t st = as_stream(stream);
+    e = launch_cov_partial(L->dtype, !ctx->force_generic, rows, B, Hkv, nc, part_S, part_sum, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "covariance launch");
+    e = launch_cov_finalize(rows, B, Hkv, nc, (flags & RK_FIT_CENTER) != 0, ct == cov_chunk_tokens(RK_BF16, true),
+                            part_S, part_sum, cov, mu, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "covariance reduction launch");
+    e = launch_subspace(U, cov, sigma, mu, solver->v0, L->keep, solver->iterations, solver->ridge, R_r, delta_mu,
+                        status, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "subspace iteration launch");
+    return RK_OK;
+}
+
 rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R, const int32_t* keep_idx,
                              float* R_r, void* stream)
 {

@@ -575,6 +575,210 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Cholesky-based subspace iteration (Alg. 1 steps 6-13, App. E), one work-group
+// per (b, h_kv), the whole T-step loop in one launch (the paper's four kernels
+// per iteration exist to cut dispatch count; here there is nothing to dispatch).
+// All arithmetic is fp64: the Gram matrix of C_q V has the squared condition of
+// C_q's leading block, which fp32 cannot factor reliably, and MI355X's fp64 vector
+// rate equals its fp32 rate for scalar FMAs.
+//
+// LDS (doubles): W [128][ks] (the basis, row stride ks = k padded so that ks % 32 == 8:
+// eight consecutive rows then start 16 banks apart), G packed lower triangle
+// [k(k+1)/2], per-column pivots, sigma, a k-vector.
+//
+// One iteration:
+//   W <- diag(sigma) C diag(sigma) W   register-tiled: thread = 4 rows x RJ columns
+//                                      (columns 32 apart), C read from global/L2 as
+//                                      float4 broadcasts, in place via registers;
+//   G <- W^T W (lower, 2x2 blocks), rho = eps tr(G) / k added to the diagonal;
+//   right-looking elimination of the stacked matrix [G; W], one barrier per column:
+//   step j uses column j (final since step j-1) to update columns > j,
+//       G[a][b] -= G[a][j] G[b][j] / G[j][j],   W[i][b] -= W[i][j] G[b][j] / G[j][j];
+//   this is the Cholesky factorisation and the solve V L^{-T} at once, with the
+//   square roots deferred: V[i][j] = W[i][j] / sqrt(pivot_j) at the end.
+constexpr int SUB_THREADS = 1024;
+constexpr int SUB_MAX_K = 104;
+
+__host__ __device__ inline int sub_row_stride(int k)
+{
+    int ks = k;
+    while (ks % 32 != 8) ++ks;
+    return ks;
+}
+__host__ __device__ inline size_t sub_lds_bytes(int k)
+{
+    return sizeof(double) * ((size_t)D * sub_row_stride(k) + (size_t)k * (k + 1) / 2 + 2 * (size_t)k + D + 8);
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+template <int RJ>
+__global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __restrict__ cov,
+                                                             const float* __restrict__ sigma,
+                                                             const float* __restrict__ mu,
+                                                             const float* __restrict__ V0, int k, int T,
+                                                             double eps, float* __restrict__ Rr,
+                                                             float* __restrict__ dmu, int32_t* __restrict__ status)
+{
+    extern __shared__ __attribute__((aligned(16))) double sub_lds[];
+    const int ks = sub_row_stride(k);
+    double* W = sub_lds;                                  // [D][ks]
+    double* G = W + (size_t)D * ks;                       // packed lower triangle
+    double* piv = G + (size_t)k * (k + 1) / 2;            // [k]
+    double* tv = piv + k;                                 // [k]
+    double* sig = tv + k;                                 // [D]
+    double* misc = sig + D;                               // [8]
+
+    const int u = blockIdx.x, tid = threadIdx.x;
+    const float* C = cov + (size_t)u * D * D;
+    const bool weighted = sigma != nullptr;
+
+    for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
+        const int i = idx / k, j = idx - i * k;
+        W[i * ks + j] = (double)V0[(size_t)u * D * k + idx];
+    }
+    for (int idx = tid; idx < D * (ks - k); idx += SUB_THREADS) {     // padding columns: keep them finite
+        const int i = idx / (ks - k), j = k + idx - i * (ks - k);
+        W[i * ks + j] = 0.0;
+    }
+    if (tid < D) sig[tid] = weighted ? (double)sigma[(size_t)u * D + tid] : 1.0;
+    __syncthreads();
+
+    const int ib = tid >> 5, jb = tid & 31;               // GEMM tile: rows 4 ib .. +3, columns jb + 32 c
+    int fail = 0;
+    for (int t = 0; t < T; ++t) {
+        // ---- W <- C_q W ----
+        if (weighted) {
+            for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
+                const int i = idx / k, j = idx - i * k;
+                W[i * ks + j] *= sig[i];
+            }
+            __syncthreads();
+        }
+        double acc[4][RJ];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < RJ; ++c) acc[r][c] = 0.0;
+        int col[RJ];
+#pragma unroll
+        for (int c = 0; c < RJ; ++c) col[c] = min(jb + 32 * c, k - 1);     // clamped: surplus lanes recompute a real column
+        for (int m0 = 0; m0 < D; m0 += 4) {
+            float4 c4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c4[r] = *(const float4*)(C + (size_t)(4 * ib + r) * D + m0);
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) {
+                double wv[RJ];
+#pragma unroll
+                for (int c = 0; c < RJ; ++c) wv[c] = W[(m0 + mm) * ks + col[c]];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float cf = mm == 0 ? c4[r].x : mm == 1 ? c4[r].y : mm == 2 ? c4[r].z : c4[r].w;
+                    const double cd = (double)cf;
+#pragma unroll
+                    for (int c = 0; c < RJ; ++c) acc[r][c] = fma(cd, wv[c], acc[r][c]);
+                }
+            }
+        }
+        __syncthreads();                                   // every thread has read the old basis
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < RJ; ++c)
+                if (jb + 32 * c < k) W[(4 * ib + r) * ks + jb + 32 * c] = acc[r][c] * sig[4 * ib + r];
+        __syncthreads();
+
+        // ---- G <- W^T W (lower triangle, 2 x 2 blocks) ----
+        const int K2 = (k + 1) >> 1, nblk = K2 * (K2 + 1) / 2;
+        for (int blk = tid; blk < nblk; blk += SUB_THREADS) {
+            int pa = (int)((sqrtf(8.f * (float)blk + 1.f) - 1.f) * 0.5f);
+            while (pa * (pa + 1) / 2 > blk) --pa;
+            while ((pa + 1) * (pa + 2) / 2 <= blk) ++pa;
+            const int pb = blk - pa * (pa + 1) / 2;
+            double s00 = 0.0, s01 = 0.0, s10 = 0.0, s11 = 0.0;
+            for (int i = 0; i < D; ++i) {
+                const double2 wa = *(const double2*)(W + i * ks + 2 * pa);
+                const double2 wb = *(const double2*)(W + i * ks + 2 * pb);
+                s00 = fma(wa.x, wb.x, s00);
+                s01 = fma(wa.x, wb.y, s01);
+                s10 = fma(wa.y, wb.x, s10);
+                s11 = fma(wa.y, wb.y, s11);
+            }
+            const int a0 = 2 * pa, a1 = a0 + 1, b0 = 2 * pb, b1 = b0 + 1;
+            G[a0 * (a0 + 1) / 2 + b0] = s00;
+            if (pa > pb) G[a0 * (a0 + 1) / 2 + b1] = s01;
+            if (a1 < k) {
+                G[a1 * (a1 + 1) / 2 + b0] = s10;
+                G[a1 * (a1 + 1) / 2 + b1] = s11;          // b1 <= a1 < k
+            }
+        }
+        __syncthreads();
+        if (tid < 64) {                                    // rho = eps tr(G) / k
+            double tr = 0.0;
+            for (int a = tid; a < k; a += 64) tr += G[a * (a + 1) / 2 + a];
+            tr = wave_sum_f64(tr);
+            const double rho = eps * tr / (double)k;
+            for (int a = tid; a < k; a += 64) G[a * (a + 1) / 2 + a] += rho;
+        }
+        __syncthreads();
+
+        // ---- elimination of [G; W], one barrier per column ----
+        const int wi = tid >> 3, wl = tid & 7;
+        for (int j = 0; j < k; ++j) {
+            const double gjj = G[j * (j + 1) / 2 + j];
+            if (!(gjj > 0.0)) { fail = t + 1; break; }    // uniform: every thread reads the same value
+            const double rinv = 1.0 / gjj;
+            const double xj = W[wi * ks + j] * rinv;
+            for (int b = j + 1 + wl; b < k; b += 8) W[wi * ks + b] = fma(-xj, G[b * (b + 1) / 2 + j], W[wi * ks + b]);
+            const int nrem = k - j - 1;
+            for (int ra = tid >> 5; ra < nrem; ra += 32) {
+                const int a = j + 1 + ra;
+                const double gaj = G[a * (a + 1) / 2 + j] * rinv;
+                for (int rb = tid & 31; rb <= ra; rb += 32) {
+                    const int b = j + 1 + rb;
+                    G[a * (a + 1) / 2 + b] = fma(-gaj, G[b * (b + 1) / 2 + j], G[a * (a + 1) / 2 + b]);
+                }
+            }
+            if (tid == 0) piv[j] = gjj;
+            __syncthreads();
+        }
+        if (fail) break;
+        if (tid < k) piv[tid] = 1.0 / sqrt(piv[tid]);
+        __syncthreads();
+        for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
+            const int i = idx / k, j = idx - i * k;
+            W[i * ks + j] *= piv[j];
+        }
+        __syncthreads();
+    }
+
+    // ---- outputs: R_k = V, delta_mu = mu - V V^T mu (Alg. 1 steps 14, 16) ----
+    if (tid == 0 && status) status[u] = fail;
+    for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
+        const int i = idx / k, j = idx - i * k;
+        Rr[(size_t)u * D * k + idx] = (float)W[i * ks + j];
+    }
+    if (tid < k) {
+        double a = 0.0;
+        for (int i = 0; i < D; ++i) a = fma(W[i * ks + tid], (double)mu[(size_t)u * D + i], a);
+        tv[tid] = a;
+    }
+    __syncthreads();
+    if (tid < D) {
+        double a = (double)mu[(size_t)u * D + tid];
+        for (int j = 0; j < k; ++j) a = fma(-W[tid * ks + j], tv[j], a);
+        dmu[(size_t)u * D + tid] = (float)a;
+    }
+    (void)misc;
+}
+
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       hipStream_t st)
@@ -588,6 +792,33 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
     }
     hipLaunchKernelGGL(eig_jacobi, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, mu, r, R, lam,
                        mask, keep_idx, Rr, dmu, sweeps);
+    return hipGetLastError();
+}
+
+int subspace_max_keep() { return SUB_MAX_K; }
+
+hipError_t launch_subspace(int U, const float* cov, const float* sigma, const float* mu, const float* V0, int k,
+                           int T, double eps, float* Rr, float* dmu, int32_t* status, hipStream_t st)
+{
+    if (k < 1 || k > SUB_MAX_K) return hipErrorInvalidValue;
+    const size_t lds = sub_lds_bytes(k);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int big = (int)sub_lds_bytes(SUB_MAX_K);
+        hipError_t e = hipFuncSetAttribute((const void*)subspace_iter<1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<3>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<4>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int rj = (k + 31) / 32;
+    switch (rj) {
+        case 1: hipLaunchKernelGGL(subspace_iter<1>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
+        case 2: hipLaunchKernelGGL(subspace_iter<2>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
+        case 3: hipLaunchKernelGGL(subspace_iter<3>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
+        default: hipLaunchKernelGGL(subspace_iter<4>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
+    }
     return hipGetLastError();
 }
 

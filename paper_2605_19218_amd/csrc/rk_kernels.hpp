@@ -19,6 +19,11 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       hipStream_t st);
+// Cholesky-based subspace iteration (Alg. 1 steps 6-13): V0 [U,d,k] -> Rr [U,d,k], dmu [U,d];
+// status [U] (optional): 0, or t+1 if iteration t met a non-positive pivot.
+int subspace_max_keep();
+hipError_t launch_subspace(int U, const float* cov, const float* sigma, const float* mu, const float* V0, int k,
+                           int T, double eps, float* Rr, float* dmu, int32_t* status, hipStream_t st);
 hipError_t launch_gather_rotation(int U, int r, const float* R, const int32_t* keep_idx, float* Rr,
                                   hipStream_t st);
 

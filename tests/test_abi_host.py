@@ -172,6 +172,23 @@ def test_dual_decode_and_text_append_validation(ctx):
     assert app(None) == rk.RK_ERR_INVALID_ARG
 
 
+def test_fit_subspace_validation(ctx):
+    lay = layout()
+    ws = rk.rk_fit_workspace_size(lay, 1000)
+    call = lambda **kw: status_of(rk.rk_fit_subspace, ctx, kw.get("lay", lay), rows(), None, rk.RK_FIT_CENTER,
+                                  kw.get("v0", PTR), kw.get("T", 5), kw.get("eps", 1e-6), kw.get("Rr", PTR), PTR, PTR,
+                                  PTR, workspace_bytes=kw.get("ws", ws))
+    assert call() == rk.RK_ERR_NO_DEVICE
+    assert call(v0=None) == rk.RK_ERR_INVALID_ARG
+    assert call(T=0) == rk.RK_ERR_INVALID_ARG
+    assert call(eps=-1.0) == rk.RK_ERR_INVALID_ARG
+    assert call(eps=float("nan")) == rk.RK_ERR_INVALID_ARG
+    assert call(Rr=None) == rk.RK_ERR_INVALID_ARG
+    assert call(ws=ws - 1) == rk.RK_ERR_WORKSPACE
+    assert call(lay=layout(keep=104)) == rk.RK_ERR_NO_DEVICE
+    assert call(lay=layout(keep=105)) == rk.RK_ERR_UNSUPPORTED
+
+
 def test_product_does_not_import_oracle():
     """The product path must not route through the CPU oracle."""
     pkg = os.path.join(ROOT, "paper_2605_19218_amd")
