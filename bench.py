@@ -234,6 +234,34 @@ def main():
         dual = dict(text_tokens=M, us_per_step=us, GBps=dbytes / (us * 1e-6) / 1e9,
                     single_path_us=sweep[str(r_main)]["us_per_step"])
 
+    # ---- the paper's default solver (Alg. 1 steps 6-13) against the full eigendecomposition ----
+    solvers = None
+    if not args.no_sweep:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg["id"] * 7919 + 5)
+        v0 = torch.randn(B, Hkv, D, r_main, device=dev, dtype=torch.float32, generator=gen)
+        sub_status = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
+
+        def do_fit_sub(st, ly):
+            fl, _ = layouts(r_main, st)
+            rk.rk_fit_subspace(ctx, fl, rk.Rows(ly["K"], L), None, rk.RK_FIT_CENTER, v0, 5, 1e-6, st["Rr"], st["mu"],
+                               st["dmu"], fit_ws, status=sub_status)
+        for i in range(max(args.warmup, 1)):
+            do_fit_sub(state[i % NL], layers[i % NL])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            do_fit_sub(state[i % NL], layers[i % NL])
+        e1.record()
+        torch.cuda.synchronize()
+        assert not sub_status.any().item(), "subspace iteration met a non-positive pivot"
+        solvers = dict(full_eigendecomposition_fit_us=stage_us["fit"]["mean"],
+                       subspace_T5_fit_us=e0.elapsed_time(e1) * 1e3 / args.steps,
+                       note="fit = covariance + solver; both in one rk_fit_* call, %d matrices of 128x128" % (B * Hkv))
+        for i in range(NL):                                  # leave the ring as the eigen route made it
+            do_fit(r_main, state[i], layers[i])
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, device=dev, dtype=torch.uint8).random_(0, 255)
         dst = torch.empty_like(src)
@@ -292,6 +320,7 @@ def main():
         "stages_us": stage_us,
         "decode_only_sweep": sweep,
         "dual_path_decode": dual,
+        "fit_solvers": solvers,
         "roofline": {"bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": committed_traffic("decode_split_mfma<64>"),
                      "kernel": "decode_split_mfma<64> + decode_merge (one rk_decode_attn call; the duration is the "

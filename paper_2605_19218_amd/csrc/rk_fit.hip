@@ -669,7 +669,8 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         int col[RJ];
 #pragma unroll
         for (int c = 0; c < RJ; ++c) col[c] = min(jb + 32 * c, k - 1);     // clamped: surplus lanes recompute a real column
-        for (int m0 = 0; m0 < D; m0 += 4) {
+#pragma unroll 2
+        for (int m0 = 0; m0 < D; m0 += 4) {          // bounded unroll: a full unroll hoists 512 registers of C
             float4 c4[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) c4[r] = *(const float4*)(C + (size_t)(4 * ib + r) * D + m0);
