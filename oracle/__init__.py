@@ -51,6 +51,7 @@ def lib():
                                            C.c_double, _D]
         L.orc_decode_dual_batch.argtypes = [_D, _D, _D, _D, _D, _D, _D, _I32, _I32, C.c_int, C.c_int, C.c_int,
                                             C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double, _D]
+        L.orc_sigma_window.argtypes = [_D, C.c_int64, C.c_int, _D]
         L.orc_subspace_iter.argtypes = [_D, C.c_int, C.c_int, _D, C.c_int, C.c_double, _D]
         L.orc_subspace_iter.restype = C.c_int
         L.orc_num_threads.restype = C.c_int
@@ -185,6 +186,16 @@ def fit(K, r, sigma=None, center=True, tok=None):
     Rr = gather_rotation(R, keep)
     dmu = delta_mu(mu, Rr)
     return dict(mu=mu, C=Cm, Cq=Cq, R=R, lam=lam, mask=mask, keep_idx=keep, Rr=Rr, dmu=dmu, sweeps=sw)
+
+
+def sigma_window(Qw):
+    """Alg. 1 step 4: per-channel l2 norm over all leading axes of Qw [..., d] (W rows, or G x W under GQA)."""
+    Qw = _f64(Qw)
+    d = Qw.shape[-1]
+    rows = Qw.size // d
+    out = np.empty(d)
+    lib().orc_sigma_window(_p(Qw), rows, d, _p(out))
+    return out
 
 
 def subspace_iter(Cq, V0, T=5, eps=1e-6):

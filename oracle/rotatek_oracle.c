@@ -234,6 +234,18 @@ void orc_compress(const double* K, int64_t n, int d, const int32_t* tok,
     }
 }
 
+/* Alg. 1 step 4 / Sec. 3.2: sigma_j = || (Q_W)_{:,j} ||_2 over the rows of the query
+ * window.  Qw [rows, d]; under grouped-query attention the caller stacks the windows
+ * of the G query heads that share the KV head (rows = G * W).                    */
+void orc_sigma_window(const double* Qw, int64_t rows, int d, double* sigma)
+{
+    for (int j = 0; j < d; ++j) {
+        double a = 0.0;
+        for (int64_t w = 0; w < rows; ++w) a += Qw[w * d + j] * Qw[w * d + j];
+        sigma[j] = sqrt(a);
+    }
+}
+
 /* ------------------------------------------------------------------------ */
 /* Alg. 1 steps 6-13 / App. E: subspace iteration with shifted Cholesky-QR.
  * V [d,k] starts as V0 (the caller's N(0,1) draw); T times:
