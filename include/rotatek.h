@@ -170,6 +170,17 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys,
                           const float* sigma, uint32_t flags, const rk_fit_out* out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Alg. 1 step 4: query-window channel weights ---------------------------------
+ * sigma[b, h_kv, j] = l2 norm over the `window` most recent prefill queries of channel
+ * j (Sec. 3.2, W = 32 in the paper), pooled over the G = H_q / H_kv query heads that
+ * share the KV head (the paper states the per-head formula; under grouped-query
+ * attention one rotation serves G heads, so their windows are stacked).  q_window:
+ * device, L->dtype, element (b, h_q, w, c) at b*stride_b + h_q*stride_h + w*stride_w
+ * + c.  sigma: device fp32 [B,H_kv,d], the `sigma` argument of rk_fit_rotation and
+ * rk_fit_subspace.  Errors: INVALID_ARG, HIP.                                      */
+rk_status rk_query_sigma(rk_ctx* ctx, const rk_layout* L, const void* q_window, int64_t stride_b,
+                         int64_t stride_h, int64_t stride_w, int32_t window, float* sigma, void* stream);
+
 /* Parameters of the subspace solver (Alg. 1 inputs T and epsilon, and the draw of step 6). */
 typedef struct {
     const float* v0;      /* device [B,H_kv,d,keep] fp32: the start basis V^(0), i.i.d. N(0,1), drawn by the caller */

@@ -27,7 +27,7 @@ EXPORTS = [
     "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
-    "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace",
+    "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace", "rk_query_sigma",
 ]
 
 
@@ -101,6 +101,7 @@ def lib():
         L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
         L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
         L.rk_fit_subspace.argtypes = [vp, PL, PR, vp, u32, C.POINTER(rk_subspace), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rk_query_sigma.argtypes = [vp, PL, vp, i64, i64, i64, i32, vp, vp]
         for name in EXPORTS:
             if name not in ("rk_status_str", "rk_last_error", "rk_fit_workspace_size", "rk_decode_workspace_size"):
                 getattr(L, name).restype = C.c_int
@@ -305,3 +306,11 @@ def rk_fit_subspace(ctx, layout: Layout, keys: Rows, sigma, flags: int, v0, iter
     _check(ctx, lib().rk_fit_subspace(ctx, C.byref(layout.c()), C.byref(keys.c()), _ptr(sigma), flags, C.byref(sv),
                                       _ptr(R_r), _ptr(mu), _ptr(delta_mu), _ptr(cov), _ptr(status),
                                       _ptr(workspace), wb, _stream(stream)))
+
+
+def rk_query_sigma(ctx, layout: Layout, q_window, window: int, sigma, strides: Optional[tuple] = None,
+                   stream=None) -> None:
+    """q_window: tensor-like [B, H_q, window, d]; strides default to its own (elements)."""
+    st = strides if strides is not None else tuple(q_window.stride()[:3])
+    _check(ctx, lib().rk_query_sigma(ctx, C.byref(layout.c()), _ptr(q_window), st[0], st[1], st[2], int(window),
+                                     _ptr(sigma), _stream(stream)))

@@ -305,6 +305,25 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     return RK_OK;
 }
 
+rk_status rk_query_sigma(rk_ctx* ctx, const rk_layout* L, const void* q_window, int64_t stride_b, int64_t stride_h,
+                         int64_t stride_w, int32_t window, float* sigma, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!q_window || !sigma) return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: NULL pointer");
+    if (window < 1) return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: window must be >= 1");
+    if (stride_b < 0 || stride_h < 0 || stride_w < D)
+        return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: strides must be non-negative, stride_w >= %d", D);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_sigma_window(L->dtype, q_window, stride_b, stride_h, stride_w, L->batch, L->n_q_heads, L->n_kv_heads,
+                            window, sigma, as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "query_sigma launch");
+    return RK_OK;
+}
+
 rk_status rk_fit_subspace(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* sigma, uint32_t flags,
                           const rk_subspace* solver, float* R_r, float* mu, float* delta_mu, float* cov_out,
                           int32_t* status, void* workspace, size_t workspace_bytes, void* stream)

@@ -780,6 +780,33 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
     (void)misc;
 }
 
+// ---------------------------------------------------------------------------
+// Alg. 1 step 4: sigma_j = ||(Q_W)_{:,j}||_2 over the window of recent queries, pooled
+// over the G query heads that share a KV head.  One block per (b, h_kv), thread =
+// channel; rows are coalesced 256- or 512-byte reads.
+template <typename T>
+__global__ __launch_bounds__(128) void sigma_window_kernel(const T* __restrict__ qw, int64_t sb, int64_t sh,
+                                                           int64_t sw, int Hq, int Hkv, int W,
+                                                           float* __restrict__ sigma)
+{
+    const int u = blockIdx.x, b = u / Hkv, hk = u % Hkv, G = Hq / Hkv, c = threadIdx.x;
+    float a0 = 0.f, a1 = 0.f;
+    for (int g = 0; g < G; ++g) {
+        const T* base = qw + (int64_t)b * sb + (int64_t)(hk * G + g) * sh + c;
+        int w = 0;
+        for (; w + 2 <= W; w += 2) {
+            const float x0 = ld_elem(base + (int64_t)w * sw), x1 = ld_elem(base + (int64_t)(w + 1) * sw);
+            a0 = fmaf(x0, x0, a0);
+            a1 = fmaf(x1, x1, a1);
+        }
+        if (w < W) {
+            const float x0 = ld_elem(base + (int64_t)w * sw);
+            a0 = fmaf(x0, x0, a0);
+        }
+    }
+    sigma[(size_t)u * D + c] = sqrtf(a0 + a1);
+}
+
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       hipStream_t st)
@@ -820,6 +847,18 @@ hipError_t launch_subspace(int U, const float* cov, const float* sigma, const fl
         case 3: hipLaunchKernelGGL(subspace_iter<3>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
         default: hipLaunchKernelGGL(subspace_iter<4>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_sigma_window(int dtype, const void* qw, int64_t sb, int64_t sh, int64_t sw, int B, int Hq,
+                               int Hkv, int W, float* sigma, hipStream_t st)
+{
+    if (dtype == 0)
+        hipLaunchKernelGGL(sigma_window_kernel<float>, dim3(B * Hkv), dim3(128), 0, st, (const float*)qw, sb, sh, sw,
+                           Hq, Hkv, W, sigma);
+    else
+        hipLaunchKernelGGL(sigma_window_kernel<bf16_t>, dim3(B * Hkv), dim3(128), 0, st, (const bf16_t*)qw, sb, sh,
+                           sw, Hq, Hkv, W, sigma);
     return hipGetLastError();
 }
 

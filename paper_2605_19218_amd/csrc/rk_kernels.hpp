@@ -24,6 +24,9 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
 int subspace_max_keep();
 hipError_t launch_subspace(int U, const float* cov, const float* sigma, const float* mu, const float* V0, int k,
                            int T, double eps, float* Rr, float* dmu, int32_t* status, hipStream_t st);
+// sigma [B,Hkv,d] from a query window [B,Hq,W,d] with element strides (sb, sh, sw)
+hipError_t launch_sigma_window(int dtype, const void* qw, int64_t sb, int64_t sh, int64_t sw, int B, int Hq,
+                               int Hkv, int W, float* sigma, hipStream_t st);
 hipError_t launch_gather_rotation(int U, int r, const float* R, const int32_t* keep_idx, float* Rr,
                                   hipStream_t st);
 

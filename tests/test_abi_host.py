@@ -189,6 +189,17 @@ def test_fit_subspace_validation(ctx):
     assert call(lay=layout(keep=105)) == rk.RK_ERR_UNSUPPORTED
 
 
+def test_query_sigma_validation(ctx):
+    lay = layout()
+    st = (8 * 32 * 128, 32 * 128, 128)
+    call = lambda q=PTR, w=32, sg=PTR, strides=st: status_of(rk.rk_query_sigma, ctx, lay, q, w, sg, strides=strides)
+    assert call() == rk.RK_ERR_NO_DEVICE
+    assert call(q=None) == rk.RK_ERR_INVALID_ARG
+    assert call(sg=None) == rk.RK_ERR_INVALID_ARG
+    assert call(w=0) == rk.RK_ERR_INVALID_ARG
+    assert call(strides=(8 * 32 * 128, 32 * 128, 64)) == rk.RK_ERR_INVALID_ARG
+
+
 def test_product_does_not_import_oracle():
     """The product path must not route through the CPU oracle."""
     pkg = os.path.join(ROOT, "paper_2605_19218_amd")
