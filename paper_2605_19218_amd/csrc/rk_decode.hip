@@ -388,13 +388,15 @@ struct DecState {
     f32x4 O[8];
 };
 
-template <int R, bool REFILL_K = false>
+template <int R>
 __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, const bf16x8 (&qh)[DecTile<R>::NFA],
                                              const bf16x8 (&ql)[DecTile<R>::NFA], s16x4 qth, s16x4 qtl, int tok0,
-                                             int t1, int g, const bf16_t* __restrict__ Ku_next = nullptr,
-                                             int tok_next = 0, int lane = 0)
+                                             int t1, int g)
 {
-    f32x4 s[2];
+    // The 16-channel tail (r % 32 == 16) accumulates in a chain of its own and is added with
+    // vector adds: a 16x16x16 MFMA that took the result of a 16x16x32 MFMA as its accumulator
+    // gave results that changed from run to run once the loads no longer stalled the chain.
+    f32x4 s[2], stail[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
         s[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -404,13 +406,15 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
             s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.kf[tb][i], ql[i], s[tb], 0, 0, 0);
         }
         if (DecTile<R>::TAIL) {
-            s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qth, s[tb], 0, 0, 0);
-            s[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qtl, s[tb], 0, 0, 0);
+            stail[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            stail[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qth, stail[tb], 0, 0, 0);
+            stail[tb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(T.kt[tb], qtl, stail[tb], 0, 0, 0);
         }
     }
-    // the K~ registers of this buffer are free once the scores are issued: refill them now,
-    // a whole softmax + P.V earlier than the V part (steady-state loop only)
-    if (REFILL_K) load_tile_k<R>(T, Ku_next, tok_next, lane);
+    if (DecTile<R>::TAIL) {
+        s[0] += stail[0];
+        s[1] += stail[1];
+    }
     if (tok0 + 32 > t1) {
         // last, partial tile of the split: rows past the end may hold anything (even NaN
         // patterns), so mask their scores and zero their Value slots
@@ -629,10 +633,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         // (s_waitcnt vmcnt) are exact and a wave never waits for its newest prefetch.
         int k = 0;
         for (; k + 3 < nk; k += 2) {
-            compute_tile<R, true>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g, Ku, tokA + 128 * (k + 2), lane);
-            load_tile_v<R>(TA, Vu, tokA + 128 * (k + 2), lane);
-            compute_tile<R, true>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g, Ku, tokA + 128 * (k + 3), lane);
-            load_tile_v<R>(TB, Vu, tokA + 128 * (k + 3), lane);
+            compute_tile<R>(TA, st, qh, ql, qth, qtl, tokA + 128 * k, t1, g);
+            load_tile<R>(TA, Ku, Vu, tokA + 128 * (k + 2), lane);
+            compute_tile<R>(TB, st, qh, ql, qth, qtl, tokA + 128 * (k + 1), t1, g);
+            load_tile<R>(TB, Ku, Vu, tokA + 128 * (k + 3), lane);
         }
         // tail: up to three tiles left (A, B, A)
         if (k < nk) {

@@ -221,6 +221,16 @@ DECODE_CASES = [
     ("empty_and_one", "bf16", 3, 4, 2, 130, [0, 1, 130], 32, False, 0),
     ("one_split", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 1),
     ("seven_splits", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 7),
+    # two splits of a 4096-token cache: 16 tiles per wave, so the pipelined steady-state loop of the
+    # split kernel runs (the short cases above only reach its prologue and tail), for every kernel width
+    ("long_r16", "bf16", 1, 4, 4, 4096, None, 16, False, 2),
+    ("long_r32", "bf16", 1, 4, 4, 4096, None, 32, False, 2),
+    ("long_r48", "bf16", 1, 4, 4, 4096, None, 48, False, 2),
+    ("long_r64_ragged", "bf16", 2, 8, 2, 4096, [4096, 3001], 64, False, 2),
+    ("long_r80", "bf16", 1, 4, 4, 4096, None, 80, False, 2),
+    ("long_r96", "bf16", 1, 4, 4, 4096, None, 96, False, 2),
+    ("long_r112", "bf16", 1, 4, 4, 4096, None, 112, False, 2),
+    ("long_r128", "bf16", 1, 4, 4, 4096, None, 128, False, 2),
 ]
 
 
