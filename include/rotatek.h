@@ -152,9 +152,10 @@ rk_status rk_cache_bytes(const rk_layout* L, size_t* k_packed_bytes, size_t* v_c
 size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens);
 /* Bytes of workspace rk_decode_attn needs (depends on batch, heads, max_seq_len). */
 size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L);
-/* The split-K plan rk_decode_attn will use: N_s and tokens per split
- * (App. C: N_s = max(1, min(ceil(S_v / BLOCK_N), 64)) on the A100; here it is
- * sized to fill 256 compute units).                                          */
+/* The split-K plan rk_decode_attn will use: N_s and the tokens of the largest split
+ * (the 128-token tiles are shared out evenly, split sizes differ by at most one
+ * tile).  App. C: N_s = max(1, min(ceil(S_v / BLOCK_N), 64)) on the A100; here it
+ * is sized to fill 256 compute units.                                         */
 rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split);
 
 /* ---- Alg. 1 steps 1-13 with the full eigendecomposition + keep-mask ---------

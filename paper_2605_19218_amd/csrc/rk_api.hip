@@ -114,7 +114,9 @@ rk_status check_text(rk_ctx* ctx, const rk_text* t, bool need_len)
     return RK_OK;
 }
 
-void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tps_out)
+// N_s and the number of 128-token tiles they share (split s gets floor(tiles / N_s) tiles, the
+// first tiles % N_s splits one more)
+void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_out)
 {
     const int G = L->n_q_heads / L->n_kv_heads;
     const bool mfma = use_mfma_decode(ctx, L);
@@ -131,10 +133,8 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tps_out
     }
     if (S > tiles) S = tiles;
     if (S < 1) S = 1;
-    const int tiles_per = (tiles + S - 1) / S;
-    const int tps = tiles_per * 128;
-    *S_out = (maxL + tps - 1) / tps;
-    *tps_out = tps;
+    *S_out = S;
+    *tiles_out = tiles;
 }
 
 hipStream_t as_stream(void* s) { return (hipStream_t)s; }
@@ -221,8 +221,8 @@ size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens)
 size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L)
 {
     if (check_layout(nullptr, L) != RK_OK) return 0;
-    int S, tps;
-    decode_plan(ctx, L, &S, &tps);
+    int S, tiles;
+    decode_plan(ctx, L, &S, &tiles);
     return align_up((size_t)L->batch * L->n_q_heads * S * (D + 2) * sizeof(float), 256);
 }
 
@@ -231,10 +231,10 @@ rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_split
     rk_status s = check_layout(nullptr, L);
     if (s != RK_OK) return s;
     if (!n_splits || !tokens_per_split) return RK_ERR_INVALID_ARG;
-    int S, tps;
-    decode_plan(ctx, L, &S, &tps);
+    int S, tiles;
+    decode_plan(ctx, L, &S, &tiles);
     *n_splits = S;
-    *tokens_per_split = tps;
+    *tokens_per_split = 128 * ((tiles + S - 1) / S);      // the largest split
     return RK_OK;
 }
 
@@ -467,11 +467,11 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
 
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
-    int S, tps;
-    decode_plan(ctx, L, &S, &tps);
+    int S, tiles;
+    decode_plan(ctx, L, &S, &tiles);
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
     e = launch_decode(L->dtype, use_mfma_decode(ctx, L), L->batch, L->n_q_heads, L->n_kv_heads, L->capacity,
-                      L->keep, S, tps, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, sc,
+                      L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, sc,
                       out, (float*)workspace, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;

@@ -31,14 +31,17 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 template <typename T>
 __global__ __launch_bounds__(128) void decode_split_generic(
     const T* __restrict__ q, const T* __restrict__ Kp, const T* __restrict__ Vc, const float* __restrict__ Rr,
-    const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq, int Hkv, int cap, int r, int tps,
+    const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
     float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S)
 {
     const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int G = Hq / Hkv, hk = hq / G, u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = min(max(seq_len[b], 0), cap);
-    const int t0 = split * tps, t1 = min(t0 + tps, L);
+    // balanced partition of the 128-token tiles: the first (tiles % S) splits get one tile more
+    const int tp = tiles_all / S, trem = tiles_all - tp * S;
+    const int t0 = 128 * (split * tp + min(split, trem));
+    const int t1 = min(128 * ((split + 1) * tp + min(split + 1, trem)), L);
     const size_t pidx = ((size_t)b * Hq + hq) * S + split;
     if (t0 >= t1) {
         if (tid == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
@@ -471,7 +474,7 @@ template <int R>
 __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vc,
     const float* __restrict__ Rr, const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq,
-    int Hkv, int cap, int tps, float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l,
+    int Hkv, int cap, int tiles_all, float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l,
     float* __restrict__ ws_acc, int S, bf16_t* __restrict__ out)
 {
     typedef DecTile<R> Tile;
@@ -498,7 +501,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int g = lane >> 4, n = lane & 15;
 
     const int L = min(max(seq_len[b], 0), cap);
-    const int t0 = split * tps, t1 = min(t0 + tps, L);
+    // balanced partition of the 128-token tiles: the first (tiles % S) splits get one tile more
+    const int tp = tiles_all / S, trem = tiles_all - tp * S;
+    const int t0 = 128 * (split * tp + min(split, trem));
+    const int t1 = min(128 * ((split + 1) * tp + min(split + 1, trem)), L);
     const bool empty = t0 >= t1;
 
     if (!empty) {
@@ -726,13 +732,13 @@ bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r % 16 == 0 
 template <int R>
 static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, const bf16_t* Kp, const bf16_t* Vc,
                                  const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv,
-                                 int cap, int tps, float sl2, float* m, float* l, float* acc, int S, bf16_t* out)
+                                 int cap, int tiles_all, float sl2, float* m, float* l, float* acc, int S, bf16_t* out)
 {
     hipLaunchKernelGGL(decode_split_mfma<R>, grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv, cap,
-                       tps, sl2, m, l, acc, S, out);
+                       tiles_all, sl2, m, l, acc, S, out);
 }
 
-hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
+hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
                          hipStream_t st)
@@ -750,7 +756,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         const bf16_t *q_ = (const bf16_t*)q, *k_ = (const bf16_t*)Kp, *v_ = (const bf16_t*)Vc;
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
-        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tps, sl2, ws_m, ws_l, \
+        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tiles_all, sl2, ws_m, ws_l, \
                                  ws_acc, S, direct ? (bf16_t*)out : nullptr);                              \
         break;
         switch (r) {
@@ -764,11 +770,11 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         dim3 grid(S, Hq, B);
         if (dtype == 0)
             hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q,
-                               (const float*)Kp, (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
+                               (const float*)Kp, (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2,
                                ws_m, ws_l, ws_acc, S);
         else
             hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
-                               (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tps, sl2,
+                               (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2,
                                ws_m, ws_l, ws_acc, S);
         e = hipGetLastError();
         if (e != hipSuccess) return e;

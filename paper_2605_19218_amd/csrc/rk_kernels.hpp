@@ -52,7 +52,8 @@ struct TextDev {
     int max_len;
 };
 // text == nullptr: visual segment only; otherwise the text segment joins the softmax in the merge kernel
-hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tps,
+// tiles_all: 128-token tiles of the longest sequence; split s takes a balanced share of them
+hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
                          hipStream_t st);
