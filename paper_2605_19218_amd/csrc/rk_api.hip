@@ -139,6 +139,22 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_o
 
 hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
+// Makes `device` current for the duration of a call and puts the caller's device back
+// afterwards: the library must not change the calling thread's current device.
+struct DeviceGuard {
+    int prev = -1;
+    hipError_t status;
+    explicit DeviceGuard(int device)
+    {
+        status = hipGetDevice(&prev);
+        if (status == hipSuccess && prev != device) status = hipSetDevice(device);
+        else if (status == hipSuccess) prev = -1;          // nothing to restore
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+    DeviceGuard(const DeviceGuard&) = delete;
+    DeviceGuard& operator=(const DeviceGuard&) = delete;
+};
+
 }  // namespace
 
 extern "C" {
@@ -173,7 +189,8 @@ rk_status rk_create(rk_ctx** out, int device)
         if (e != hipSuccess) { delete c; return RK_ERR_HIP; }
         c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
         const size_t tb = (size_t)APP_TICKETS * sizeof(int32_t);
-        if (hipSetDevice(device) != hipSuccess || hipMalloc((void**)&c->tickets, tb) != hipSuccess) {
+        DeviceGuard dev(device);
+        if (dev.status != hipSuccess || hipMalloc((void**)&c->tickets, tb) != hipSuccess) {
             delete c;
             return RK_ERR_HIP;
         }
@@ -190,7 +207,10 @@ rk_status rk_create(rk_ctx** out, int device)
 rk_status rk_destroy(rk_ctx* ctx)
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
-    if (ctx->tickets) (void)hipFree(ctx->tickets);
+    if (ctx->tickets) {
+        DeviceGuard dev(ctx->device);
+        (void)hipFree(ctx->tickets);
+    }
     delete ctx;
     return RK_OK;
 }
@@ -257,7 +277,8 @@ rk_status rk_unpack_cache(rk_ctx* ctx, const rk_layout* L, const void* k_packed,
     if ((k_rows && !k_packed) || (v_rows && !v_cache) || (!k_rows && !v_rows))
         return fail(ctx, RK_ERR_INVALID_ARG, "unpack: nothing to do or source missing");
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_unpack(L->dtype, L->batch * L->n_kv_heads, L->capacity, L->keep, k_packed, v_cache, k_rows, v_rows,
                       as_stream(stream));
@@ -282,7 +303,8 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
         return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
 
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const int B = L->batch, Hkv = L->n_kv_heads, U = B * Hkv;
     const int ct = cov_chunk_tokens(L->dtype, !ctx->force_generic);
@@ -316,7 +338,8 @@ rk_status rk_query_sigma(rk_ctx* ctx, const rk_layout* L, const void* q_window, 
     if (stride_b < 0 || stride_h < 0 || stride_w < D)
         return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: strides must be non-negative, stride_w >= %d", D);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_sigma_window(L->dtype, q_window, stride_b, stride_h, stride_w, L->batch, L->n_q_heads, L->n_kv_heads,
                             window, sigma, as_stream(stream));
@@ -346,7 +369,8 @@ rk_status rk_fit_subspace(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
         return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
 
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     const int B = L->batch, Hkv = L->n_kv_heads, U = B * Hkv;
     const int ct = cov_chunk_tokens(L->dtype, !ctx->force_generic);
@@ -377,7 +401,8 @@ rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R, co
     if (s != RK_OK) return s;
     if (!R || !keep_idx || !R_r) return fail(ctx, RK_ERR_INVALID_ARG, "gather_rotation: NULL pointer");
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_gather_rotation(L->batch * L->n_kv_heads, L->keep, R, keep_idx, R_r, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "gather launch");
@@ -407,7 +432,8 @@ rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, cons
         return fail(ctx, RK_ERR_CAPACITY, "compress: %d rows exceed capacity %d", keys->n_tokens, L->capacity);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
 
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     hipStream_t st = as_stream(stream);
     e = launch_compress(L->dtype, !ctx->force_generic, to_dev(keys), L->batch, L->n_kv_heads, L->capacity, L->keep,
@@ -432,7 +458,8 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
         return fail(ctx, RK_ERR_CAPACITY, "append: %d + 1 rows exceed capacity %d", L->max_seq_len, L->capacity);
     if (L->batch > APP_TICKETS) return fail(ctx, RK_ERR_UNSUPPORTED, "append: batch too large");
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_append(L->dtype, L->batch, L->n_kv_heads, L->capacity, L->keep, k_new, v_new, R_r, k_packed,
                       v_cache, seq_len, ctx->tickets, as_stream(stream));
@@ -465,7 +492,8 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
         return fail(ctx, RK_ERR_WORKSPACE, "decode workspace: need %zu bytes, 16-byte aligned", need);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
 
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     int S, tiles;
     decode_plan(ctx, L, &S, &tiles);
@@ -509,7 +537,8 @@ rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, c
         return fail(ctx, RK_ERR_CAPACITY, "append_text: %d + 1 rows exceed capacity %d", text->max_len,
                     text->capacity);
     if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
-    hipError_t e = hipSetDevice(ctx->device);
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
     e = launch_append_text(L->dtype, L->batch, L->n_kv_heads, text->capacity, k_new, v_new, text->k, text->v,
                            text->stride_b, text->stride_h, text->stride_t, text->len, as_stream(stream));

@@ -5,9 +5,29 @@
 //   eig_jacobi      : C_q = (sigma sigma^T) .* C (step 5 / Eq. 4), all eigenpairs by
 //                     parallel two-sided Jacobi resident in LDS, then the keep-mask,
 //                     R_r and delta_mu (step 15)
+#include <mutex>
+#include <set>
+#include <utility>
 #include "rk_kernels.hpp"
 
 namespace rk {
+
+// Kernels that use more than 64 KB of dynamic LDS need the limit raised once per (device,
+// kernel); launches may come from several host threads and contexts.
+static hipError_t allow_dynamic_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({dev, kernel})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.insert({dev, kernel});
+    return e;
+}
+
 
 // ---------------------------------------------------------------------------
 // Plain covariance partial: 256 threads, thread (ty, tx) owns the 8x8 outputs
@@ -541,16 +561,9 @@ hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, 
 {
     dim3 grid(n_chunks, Hkv, B);
     if (mfma && dtype == 1) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void*)cov_partial_mfma<true>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)COVM_LDS_BYTES);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute((const void*)cov_partial_mfma<false>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)COVM_LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = allow_dynamic_lds(rows.tok_idx ? (const void*)cov_partial_mfma<true>
+                                                      : (const void*)cov_partial_mfma<false>, COVM_LDS_BYTES);
+        if (e != hipSuccess) return e;
         if (rows.tok_idx)
             hipLaunchKernelGGL(cov_partial_mfma<true>, grid, dim3(256), COVM_LDS_BYTES, st, rows, Hkv, n_chunks, part_S,
                                part_sum);
@@ -811,13 +824,8 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)eig_jacobi, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)EIG_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    hipError_t e = allow_dynamic_lds((const void*)eig_jacobi, EIG_LDS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(eig_jacobi, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, mu, r, R, lam,
                        mask, keep_idx, Rr, dmu, sweeps);
     return hipGetLastError();
@@ -830,17 +838,11 @@ hipError_t launch_subspace(int U, const float* cov, const float* sigma, const fl
 {
     if (k < 1 || k > SUB_MAX_K) return hipErrorInvalidValue;
     const size_t lds = sub_lds_bytes(k);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const int big = (int)sub_lds_bytes(SUB_MAX_K);
-        hipError_t e = hipFuncSetAttribute((const void*)subspace_iter<1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<3>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)subspace_iter<4>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int rj = (k + 31) / 32;
+    const void* fn = rj == 1 ? (const void*)subspace_iter<1> : rj == 2 ? (const void*)subspace_iter<2>
+                   : rj == 3 ? (const void*)subspace_iter<3> : (const void*)subspace_iter<4>;
+    hipError_t e = allow_dynamic_lds(fn, sub_lds_bytes(SUB_MAX_K));
+    if (e != hipSuccess) return e;
     switch (rj) {
         case 1: hipLaunchKernelGGL(subspace_iter<1>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
         case 2: hipLaunchKernelGGL(subspace_iter<2>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
