@@ -621,7 +621,8 @@ __host__ __device__ inline int sub_row_stride(int k)
 }
 __host__ __device__ inline size_t sub_lds_bytes(int k)
 {
-    return sizeof(double) * ((size_t)D * sub_row_stride(k) + (size_t)k * (k + 1) / 2 + 2 * (size_t)k + D + 8);
+    const size_t kpad = 16 * (size_t)((k + 15) / 16);
+    return sizeof(double) * ((size_t)D * sub_row_stride(k) + (size_t)k * (k + 1) / 2 + 2 * (size_t)(k + 4) + D + 2 * kpad);
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v)
@@ -631,7 +632,78 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
-template <int RJ>
+// 1 / g for g > 0 in double: hardware estimate + two Newton steps (the full IEEE division
+// sequence is four times as long and sits on the critical path of every elimination step)
+__device__ __forceinline__ double fast_rcp_f64(double g)
+{
+    double r = __builtin_amdgcn_rcp(g);
+    double e = fma(-g, r, 1.0);
+    r = fma(r, e, r);
+    e = fma(-g, r, 1.0);
+    return fma(r, e, r);
+}
+
+// value of lane (quad base + PJ) for every lane of the quad
+template <int PJ>
+__device__ __forceinline__ double quad_bcast(double v)
+{
+    constexpr int ctrl = PJ | (PJ << 2) | (PJ << 4) | (PJ << 6);       // DPP quad_perm [PJ, PJ, PJ, PJ]
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_mov_dpp(lo, ctrl, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_mov_dpp(hi, ctrl, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Right-looking elimination of the stacked matrix [W; G] with the rows in registers: thread
+// (row, part) holds x[c] = element (row, part + 4 c); rows 0..127 are W, rows 128.. are G (k
+// padded to a multiple of 4 with an identity block, so that every step exists).  Step
+// j = 4 CJ + PJ: the four owners of stack row 128 + j (= row j of G, final since step j-1)
+// publish it scaled by 1 / G[j][j] (the raw pivot goes to slot j), one barrier, then every
+// thread subtracts (its own column-j element) x (the published row) from its columns > j.
+// The code is straight-line per block of four steps; a pivot that is not positive is only
+// recorded, the remaining steps then run on meaningless numbers and the caller discards the
+// result (early exits here made the register allocator spill the whole row).
+template <int NCOL, int CJ, int PJ>
+__device__ __forceinline__ void elim_step(double (&x)[NCOL], double* __restrict__ rb, double* __restrict__ piv,
+                                          int row, int part, int tid, bool& bad)
+{
+    constexpr int j = 4 * CJ + PJ;
+    if (row == D + j) {
+        const double gjj = quad_bcast<PJ>(x[CJ]);
+        const double rinv = fast_rcp_f64(gjj);
+        if (part == PJ) rb[j] = gjj;
+        else if (part > PJ) rb[4 * CJ + part] = x[CJ] * rinv;
+#pragma unroll
+        for (int c = CJ + 1; c < NCOL; ++c) rb[4 * c + part] = x[c] * rinv;
+    }
+    __syncthreads();
+    const double gjj = rb[j];
+    bad = bad || !(gjj > 0.0);
+    if (tid == 0) piv[j] = gjj;
+    const double f = -quad_bcast<PJ>(x[CJ]);
+    if (part > PJ) x[CJ] = fma(f, rb[4 * CJ + part], x[CJ]);
+#pragma unroll
+    for (int c = CJ + 1; c < NCOL; ++c) x[c] = fma(f, rb[4 * c + part], x[c]);
+}
+
+// Blocks CJ, CJ + 1, ... while they exist (4 CJ < kp4, uniform); nested so that the register
+// values only merge once, after the last block.
+template <int NCOL, int CJ>
+__device__ __forceinline__ void elim_block(double (&x)[NCOL], double* __restrict__ rowbuf2, double* __restrict__ piv,
+                                           int kp4, int kpad, int row, int part, int tid, bool& bad)
+{
+    if constexpr (CJ < NCOL) {
+        if (4 * CJ < kp4) {
+            elim_step<NCOL, CJ, 0>(x, rowbuf2, piv, row, part, tid, bad);
+            elim_step<NCOL, CJ, 1>(x, rowbuf2 + kpad, piv, row, part, tid, bad);
+            elim_step<NCOL, CJ, 2>(x, rowbuf2, piv, row, part, tid, bad);
+            elim_step<NCOL, CJ, 3>(x, rowbuf2 + kpad, piv, row, part, tid, bad);
+            elim_block<NCOL, CJ + 1>(x, rowbuf2, piv, kp4, kpad, row, part, tid, bad);
+        }
+    }
+}
+
+template <int KB>
 __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __restrict__ cov,
                                                              const float* __restrict__ sigma,
                                                              const float* __restrict__ mu,
@@ -643,10 +715,13 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
     const int ks = sub_row_stride(k);
     double* W = sub_lds;                                  // [D][ks]
     double* G = W + (size_t)D * ks;                       // packed lower triangle
-    double* piv = G + (size_t)k * (k + 1) / 2;            // [k]
-    double* tv = piv + k;                                 // [k]
-    double* sig = tv + k;                                 // [D]
-    double* misc = sig + D;                               // [8]
+    double* piv = G + (size_t)k * (k + 1) / 2;            // [k + 4] (k padded to a multiple of 4)
+    double* tv = piv + k + 4;                             // [k + 4]
+    double* sig = tv + k + 4;                             // [D]
+    double* rowbuf2 = sig + D;                            // [2][kpad]: the published pivot row, double-buffered
+    constexpr int RJ = (KB + 1) / 2;                      // GEMM columns per thread (32 apart)
+    constexpr int NCOL = 4 * KB;                          // elimination: columns per thread (4 apart)
+    const int kpad = 4 * NCOL;
 
     const int u = blockIdx.x, tid = threadIdx.x;
     const float* C = cov + (size_t)u * D * D;
@@ -743,34 +818,39 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         }
         __syncthreads();
 
-        // ---- elimination of [G; W], one barrier per column ----
-        const int wi = tid >> 3, wl = tid & 7;
-        for (int j = 0; j < k; ++j) {
-            const double gjj = G[j * (j + 1) / 2 + j];
-            if (!(gjj > 0.0)) { fail = t + 1; break; }    // uniform: every thread reads the same value
-            const double rinv = 1.0 / gjj;
-            const double xj = W[wi * ks + j] * rinv;
-            for (int b = j + 1 + wl; b < k; b += 8) W[wi * ks + b] = fma(-xj, G[b * (b + 1) / 2 + j], W[wi * ks + b]);
-            const int nrem = k - j - 1;
-            for (int ra = tid >> 5; ra < nrem; ra += 32) {
-                const int a = j + 1 + ra;
-                const double gaj = G[a * (a + 1) / 2 + j] * rinv;
-                for (int rb = tid & 31; rb <= ra; rb += 32) {
-                    const int b = j + 1 + rb;
-                    G[a * (a + 1) / 2 + b] = fma(-gaj, G[b * (b + 1) / 2 + j], G[a * (a + 1) / 2 + b]);
+        // ---- elimination of [W; G] with the rows in registers, one barrier per column ----
+        {
+            const int row = tid >> 2, part = tid & 3;      // stacked row: W rows 0..127, then G rows
+            const int kp4 = (k + 3) & ~3;                  // G padded with an identity block to a multiple of 4
+            double x[NCOL];
+#pragma unroll
+            for (int c = 0; c < NCOL; ++c) {
+                const int bcol = part + 4 * c;
+                double v = 0.0;
+                if (row < D) {
+                    if (bcol < k) v = W[row * ks + bcol];
+                } else if (row < D + kp4) {
+                    const int a = row - D, hi = max(a, bcol), lo = min(a, bcol);
+                    if (hi < k) v = G[hi * (hi + 1) / 2 + lo];
+                    else if (a == bcol) v = 1.0;
+                }
+                x[c] = v;
+            }
+            bool bad = false;
+            elim_block<NCOL, 0>(x, rowbuf2, piv, kp4, kpad, row, part, tid, bad);
+            if (bad) { fail = t + 1; break; }              // uniform: every thread saw the same pivots
+            __syncthreads();                               // piv complete
+            if (tid < k) tv[tid] = 1.0 / sqrt(piv[tid]);
+            __syncthreads();
+            if (row < D) {
+#pragma unroll
+                for (int c = 0; c < NCOL; ++c) {
+                    const int bcol = part + 4 * c;
+                    if (bcol < k) W[row * ks + bcol] = x[c] * tv[bcol];
                 }
             }
-            if (tid == 0) piv[j] = gjj;
             __syncthreads();
         }
-        if (fail) break;
-        if (tid < k) piv[tid] = 1.0 / sqrt(piv[tid]);
-        __syncthreads();
-        for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
-            const int i = idx / k, j = idx - i * k;
-            W[i * ks + j] *= piv[j];
-        }
-        __syncthreads();
     }
 
     // ---- outputs: R_k = V, delta_mu = mu - V V^T mu (Alg. 1 steps 14, 16) ----
@@ -790,7 +870,6 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         for (int j = 0; j < k; ++j) a = fma(-W[tid * ks + j], tv[j], a);
         dmu[(size_t)u * D + tid] = (float)a;
     }
-    (void)misc;
 }
 
 // ---------------------------------------------------------------------------
@@ -838,17 +917,20 @@ hipError_t launch_subspace(int U, const float* cov, const float* sigma, const fl
 {
     if (k < 1 || k > SUB_MAX_K) return hipErrorInvalidValue;
     const size_t lds = sub_lds_bytes(k);
-    const int rj = (k + 31) / 32;
-    const void* fn = rj == 1 ? (const void*)subspace_iter<1> : rj == 2 ? (const void*)subspace_iter<2>
-                   : rj == 3 ? (const void*)subspace_iter<3> : (const void*)subspace_iter<4>;
-    hipError_t e = allow_dynamic_lds(fn, sub_lds_bytes(SUB_MAX_K));
-    if (e != hipSuccess) return e;
-    switch (rj) {
-        case 1: hipLaunchKernelGGL(subspace_iter<1>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
-        case 2: hipLaunchKernelGGL(subspace_iter<2>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
-        case 3: hipLaunchKernelGGL(subspace_iter<3>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
-        default: hipLaunchKernelGGL(subspace_iter<4>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, Rr, dmu, status); break;
+    const int kb = (k + 15) / 16;
+#define RK_SUB(KBV)                                                                                          \
+    case KBV: {                                                                                              \
+        hipError_t e = allow_dynamic_lds((const void*)subspace_iter<KBV>, sub_lds_bytes(SUB_MAX_K));         \
+        if (e != hipSuccess) return e;                                                                       \
+        hipLaunchKernelGGL(subspace_iter<KBV>, dim3(U), dim3(SUB_THREADS), lds, st, cov, sigma, mu, V0, k, T, eps, \
+                           Rr, dmu, status);                                                                 \
+        break;                                                                                               \
     }
+    switch (kb) {
+        RK_SUB(1) RK_SUB(2) RK_SUB(3) RK_SUB(4) RK_SUB(5) RK_SUB(6) RK_SUB(7)
+        default: return hipErrorInvalidValue;
+    }
+#undef RK_SUB
     return hipGetLastError();
 }
 
