@@ -359,6 +359,61 @@ __global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n
     }
 }
 
+// Reduction of tile-format partials (written by cov_partial_mfma) in their own order: thread =
+// one (tile, i, lane) position, so every load is coalesced across the wave and all chunks of a
+// position are in flight together; the element goes to cov[r][c] and, for off-diagonal tiles
+// and off-diagonal elements of diagonal tiles, cov[c][r] is written by its own position or
+// mirrored here.  Grid (40, U): 10 tiles x 1024 positions per (b, h_kv).
+__global__ __launch_bounds__(256) void cov_finalize_tiled(RowsDev rows, int Hkv, int n_chunks, int center,
+                                                          const float* __restrict__ part_S,
+                                                          const float* __restrict__ part_sum,
+                                                          float* __restrict__ cov, float* __restrict__ mu_out)
+{
+    const int u = blockIdx.y, b = u / Hkv;
+    const int tid = threadIdx.x;
+    const int n_b = rows_count(rows, b);
+    __shared__ double smu[D];
+    const int posn = blockIdx.x * 256 + tid;            // [tile][i][lane], 0 .. 10239
+    const float* pS = part_S + (size_t)u * n_chunks * (D * D) + posn;
+    // the first 8 chunks of this position: requested before the mean is formed
+    float v0[8];
+    const int first = min(n_chunks, 8);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v0[k] = pS[(size_t)min(k, first - 1) * (D * D)];
+    if (tid < D) {
+        const float* ps = part_sum + (size_t)u * n_chunks * D + tid;
+        double s = 0.0;
+        for (int ch = 0; ch < n_chunks; ++ch) s += (double)ps[(size_t)ch * D];
+        const double m = n_b > 0 ? s / (double)n_b : 0.0;
+        smu[tid] = m;
+        if (blockIdx.x == 0) mu_out[(size_t)u * D + tid] = (float)m;
+    }
+    __syncthreads();
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += k < first ? (double)v0[k] : 0.0;          // ascending chunk order
+    for (int ch = 8; ch < n_chunks; ch += 8) {
+        float v[8];
+        const int last = n_chunks - 1;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = pS[(size_t)min(ch + k, last) * (D * D)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += ch + k < n_chunks ? (double)v[k] : 0.0;
+    }
+    // inverse of covm_tile_index
+    const int t = posn >> 10, i = (posn >> 6) & 15, lane = posn & 63;
+    int br = 0, rem = t;
+    while (rem >= 4 - br) { rem -= 4 - br; ++br; }
+    const int bc = br + rem;
+    const int mr = 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), mc = lane & 31;
+    const int rch = ((mr & 15) << 3) | (br << 1) | (mr >> 4);
+    const int cch = ((mc & 15) << 3) | (bc << 1) | (mc >> 4);
+    if (center) acc -= (double)n_b * (smu[rch] * smu[cch]);
+    float* Cu = cov + (size_t)u * D * D;
+    Cu[rch * D + cch] = (float)acc;
+    if (br != bc) Cu[cch * D + rch] = (float)acc;       // diagonal tiles hold both (r, c) and (c, r)
+}
+
 // ---------------------------------------------------------------------------
 // Batched symmetric eigensolver: one 1024-thread work-group per 128x128 matrix,
 // A and the accumulated eigenvectors V both resident in LDS (2 x 64 KB).
@@ -583,8 +638,12 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
                                const float* part_S, const float* part_sum, float* cov, float* mu,
                                hipStream_t st)
 {
-    hipLaunchKernelGGL(cov_finalize, dim3(8, B * Hkv), dim3(256), 0, st, rows, Hkv, n_chunks, center ? 1 : 0,
-                       tiled ? 1 : 0, part_S, part_sum, cov, mu);
+    if (tiled)
+        hipLaunchKernelGGL(cov_finalize_tiled, dim3(40, B * Hkv), dim3(256), 0, st, rows, Hkv, n_chunks,
+                           center ? 1 : 0, part_S, part_sum, cov, mu);
+    else
+        hipLaunchKernelGGL(cov_finalize, dim3(8, B * Hkv), dim3(256), 0, st, rows, Hkv, n_chunks, center ? 1 : 0,
+                           0, part_S, part_sum, cov, mu);
     return hipGetLastError();
 }
 
