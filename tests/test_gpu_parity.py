@@ -231,6 +231,17 @@ DECODE_CASES = [
     ("long_r96", "bf16", 1, 4, 4, 4096, None, 96, False, 2),
     ("long_r112", "bf16", 1, 4, 4, 4096, None, 112, False, 2),
     ("long_r128", "bf16", 1, 4, 4, 4096, None, 128, False, 2),
+    # head-group shapes: G = 8 (64 query / 8 KV heads), G = 16 (exactly one MFMA column block), G = 32 (two blocks)
+    ("g8_llama_like", "bf16", 1, 64, 8, 900, None, 64, False, 0),
+    ("g16_full_block", "bf16", 2, 16, 1, 1500, [1500, 97], 32, False, 0),
+    ("g32_two_blocks", "bf16", 1, 32, 1, 640, None, 64, False, 3),
+    # generic kernels at the ends of the range of r, both storage types
+    ("r1_generic", "bf16", 1, 4, 2, 300, None, 1, False, 0),
+    ("r8_generic", "bf16", 1, 4, 2, 300, None, 8, False, 0),
+    ("r127_f32", "f32", 1, 2, 1, 257, None, 127, False, 0),
+    ("r128_f32_dense", "f32", 1, 2, 2, 256, None, 128, False, 2),
+    # lengths at tile and split edges
+    ("edges", "bf16", 6, 4, 2, 1025, [1025, 1024, 1023, 129, 128, 127], 64, False, 0),
 ]
 
 
