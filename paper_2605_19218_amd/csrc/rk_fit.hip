@@ -456,7 +456,10 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
     int* skeep = (int*)(red + 64);        // [128]
 
     const int u = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;   // 16 waves
+    const int tid = threadIdx.x, lane = tid & 63;
+    // wave-uniform (scalar registers): the pair indices and row offsets of a wave's blocks are then
+    // computed once per wave on the scalar unit instead of once per lane
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // 16 waves
     const float* C = cov + (size_t)u * D * D;
     const float* sg = sigma ? sigma + (size_t)u * D : nullptr;
 
@@ -522,36 +525,57 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
             int p2, q2;
             rr_pair(round, lane, p2, q2);
             const float s2 = rs[lane], tau2 = rtau[lane];
-            // A <- J^T A J : 64 x 64 blocks, wave handles pair-rows k = wave + 16 it
+            // A <- J^T A J : 64 x 64 blocks, wave handles pair-rows k = wave + 16 it;
+            // V <- V J     : 128 rows x 64 pairs.
+            // Software-pipelined by hand: the loads of block it + 1 are issued before the
+            // arithmetic and the stores of block it (every element belongs to exactly one thread
+            // per round, so the order is free; the compiler cannot know that and would keep each
+            // block's load -> math -> store chain serial, leaving the LDS idle while the VALU
+            // works and vice versa).
+            int pn, qn;
+            rr_pair(round, wave, pn, qn);
+            float n00 = A[pn * D + p2], n01 = A[pn * D + q2], n10 = A[qn * D + p2], n11 = A[qn * D + q2];
+            float ns1 = rs[wave], ntau1 = rtau[wave];
+            float nv0 = 0.f, nv1 = 0.f;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
-                int k = wave + 16 * it;
-                int p, q;
-                rr_pair(round, k, p, q);
-                float s1 = rs[k], tau1 = rtau[k];
-                float a00 = A[p * D + p2], a01 = A[p * D + q2];
-                float a10 = A[q * D + p2], a11 = A[q * D + q2];
+                const int k = wave + 16 * it;
+                const int p = pn, q = qn;
+                const float a00 = n00, a01 = n01, a10 = n10, a11 = n11, s1 = ns1, tau1 = ntau1;
+                if (it < 3) {
+                    rr_pair(round, k + 16, pn, qn);
+                    n00 = A[pn * D + p2]; n01 = A[pn * D + q2];
+                    n10 = A[qn * D + p2]; n11 = A[qn * D + q2];
+                    ns1 = rs[k + 16]; ntau1 = rtau[k + 16];
+                } else {
+                    nv0 = V[wave * D + p2];
+                    nv1 = V[wave * D + q2];
+                }
                 // rows p, q : J^T from the left
                 float b00 = a00 - s1 * (a10 + tau1 * a00), b01 = a01 - s1 * (a11 + tau1 * a01);
                 float b10 = a10 + s1 * (a00 - tau1 * a10), b11 = a11 + s1 * (a01 - tau1 * a11);
                 // columns p', q' : J from the right
                 float e00 = b00 - s2 * (b01 + tau2 * b00), e01 = b01 + s2 * (b00 - tau2 * b01);
                 float e10 = b10 - s2 * (b11 + tau2 * b10), e11 = b11 + s2 * (b10 - tau2 * b11);
-                if (k == lane) {           // the pair's own block: annihilated exactly
-                    float t = rt[k];
-                    e00 = a00 - t * a01;
-                    e11 = a11 + t * a01;
-                    e01 = 0.f;
-                    e10 = 0.f;
+                {                          // the pair's own block: annihilated exactly (branch-free)
+                    const bool own = k == lane;
+                    const float t = rt[k];
+                    e00 = own ? a00 - t * a01 : e00;
+                    e11 = own ? a11 + t * a01 : e11;
+                    e01 = own ? 0.f : e01;
+                    e10 = own ? 0.f : e10;
                 }
                 A[p * D + p2] = e00; A[p * D + q2] = e01;
                 A[q * D + p2] = e10; A[q * D + q2] = e11;
             }
-            // V <- V J : 128 rows x 64 pairs
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
-                int i = wave + 16 * it;
-                float v0 = V[i * D + p2], v1 = V[i * D + q2];
+                const int i = wave + 16 * it;
+                const float v0 = nv0, v1 = nv1;
+                if (it < 7) {
+                    nv0 = V[(i + 16) * D + p2];
+                    nv1 = V[(i + 16) * D + q2];
+                }
                 V[i * D + p2] = v0 - s2 * (v1 + tau2 * v0);
                 V[i * D + q2] = v1 + s2 * (v0 - tau2 * v1);
             }
