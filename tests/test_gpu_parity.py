@@ -151,13 +151,16 @@ def test_eig_invariants_and_mask(ctx, with_sigma):
 
 
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype,r,generic", [
-    ("f32", 32, False), ("bf16", 64, False), ("bf16", 64, True), ("bf16", 48, False), ("bf16", 16, False),
-    ("bf16", 96, False), ("bf16", 128, False), ("bf16", 37, False),
+@pytest.mark.parametrize("dtype,r,generic,L,lengths", [
+    ("f32", 32, False, 333, [333, 70]), ("bf16", 64, False, 333, [333, 70]), ("bf16", 64, True, 333, [333, 70]),
+    ("bf16", 48, False, 333, [333, 70]), ("bf16", 16, False, 333, [333, 70]), ("bf16", 96, False, 333, [333, 70]),
+    ("bf16", 128, False, 333, [333, 70]), ("bf16", 37, False, 333, [333, 70]),
+    ("bf16", 80, False, 333, [333, 70]), ("bf16", 112, False, 333, [333, 70]),
+    # several 256-token passes per work-group and a ragged end inside the last pass
+    ("bf16", 64, False, 2500, [2500, 1100]), ("bf16", 48, False, 1300, [1300, 1025]),
 ])
-def test_compress_parity(ctx, dtype, r, generic):
-    B, Hkv, L = 2, 2, 333
-    lengths = [333, 70]
+def test_compress_parity(ctx, dtype, r, generic, L, lengths):
+    B, Hkv = 2, 2
     data = layer(B, Hkv, Hkv, L, dtype, 13, lengths=lengths)
     rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, int(generic))
     try:
