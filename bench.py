@@ -234,6 +234,45 @@ def main():
         dual = dict(text_tokens=M, us_per_step=us, GBps=dbytes / (us * 1e-6) / 1e9,
                     single_path_us=sweep[str(r_main)]["us_per_step"])
 
+    # ---- the per-token serving loop (append + decode on every layer of the ring), eager and as a HIP graph ----
+    loop = None
+    if not args.no_sweep:
+        NTOK = 16                                              # tokens generated per measurement (cap = L + 64)
+        bound = L + 2 * NTOK + 2                               # host bound that covers warm-up, eager and replayed tokens
+
+        def token_step(stream=None):
+            for i in range(NL):
+                st, ly = state[i], layers[i]
+                al = rk.Layout(B, Hq, Hkv, r_main, rk.RK_BF16, cap, bound - 1, seq_len=st["seq_len"])
+                dl = rk.Layout(B, Hq, Hkv, r_main, rk.RK_BF16, cap, bound, seq_len=st["seq_len"])
+                rk.rk_append(ctx, al, ly["k_new"], ly["v_new"], st["Rr"], st["Kp"], st["Vc"], st["seq_len"], stream=stream)
+                rk.rk_decode_attn(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], 0.0, st["out"], dec_ws,
+                                  stream=stream)
+        for i in range(NL):
+            do_compress(r_main, state[i], layers[i])           # lengths back to L
+        token_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(NTOK):
+            token_step()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) * 1e6 / (NTOK * NL)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(g, stream=side):
+            token_step(stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(NTOK - 1):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) * 1e6 / ((NTOK - 1) * NL)
+        assert int(state[0]["seq_len"][0]) == L + 2 * NTOK, "token loop lost count"
+        loop = dict(layers=NL, tokens=NTOK, eager_us_per_layer=eager_us, graph_us_per_layer=graph_us,
+                    note="wall clock per (rk_append + rk_decode_attn) of one layer, host launch overhead included; "
+                         "graph = one captured token step (3 kernels x %d layers) replayed" % NL)
+        del g
+
     # ---- the paper's default solver (Alg. 1 steps 6-13) against the full eigendecomposition ----
     solvers = None
     if not args.no_sweep:
@@ -321,6 +360,7 @@ def main():
         "decode_only_sweep": sweep,
         "dual_path_decode": dual,
         "fit_solvers": solvers,
+        "token_loop": loop,
         "roofline": {"bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": committed_traffic("decode_split_mfma<64>"),
                      "kernel": "decode_split_mfma<64> + decode_merge (one rk_decode_attn call; the duration is the "
