@@ -58,8 +58,8 @@ def committed_traffic(kernel_tag):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by "
-              "(batch item, KV head) with no exchange; see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (every unit of state is per "
+              "(batch item, KV head), so more GPUs would each take a share of heads with no exchange)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
