@@ -130,6 +130,9 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_o
         long target = 2L * n_cu;          // two 4-wave work-groups per compute unit
         S = (int)((target + units - 1) / units);
         if (S > 64) S = 64;
+        // a split shorter than 512 tokens (four 32-token tiles per wave) no longer amortises its
+        // prologue and its partial: measured optimum on short caches and small batches
+        if (S > tiles / 4) S = tiles / 4;
     }
     if (S > tiles) S = tiles;
     if (S < 1) S = 1;
