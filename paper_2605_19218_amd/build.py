@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import re
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -19,19 +20,26 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def _report_scratch(stderr_lines) -> None:
+    """A kernel that spills registers to scratch memory runs an order of magnitude slower: say so loudly."""
+    name = None
+    for l in stderr_lines:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l:
+            n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if n > 0:
+                print(f"WARNING: kernel {name} uses {n} bytes/lane of scratch (register spills)")
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)
-    # the host pass warns that it does not know the packed-fp32 feature: harmless
+    # the host pass warns that it does not know the packed-fp32 feature: harmless.  The resource
+    # remarks come with source-context lines ("  105 | {" / "      | ^"): keep only real diagnostics.
     lines = [l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l]
     remarks = [l for l in lines if "-Rpass-analysis=kernel-resource-usage" in l]
-    # (the remarks come with source-context lines "  105 | {" / "      | ^": drop those as well)
     ctx = re.compile(r"^\s*\d*\s*\|")
     err = "\n".join(l for l in lines if "-Rpass-analysis=kernel-resource-usage" not in l and not ctx.match(l)
                     and "remarks generated" not in l and "warning generated" not in l)
@@ -39,15 +47,23 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    # a kernel that spills registers to scratch memory runs an order of magnitude slower: say so loudly
-    name = None
-    for l in remarks:
-        if "Function Name:" in l:
-            name = l.split("Function Name:")[1].split("[")[0].strip()
-        elif "ScratchSize [bytes/lane]:" in l:
-            n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
-            if n > 0:
-                print(f"WARNING: kernel {name} uses {n} bytes/lane of scratch (register spills)")
+    return remarks
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel) and link librotatek.so."""
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    common = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+        jobs = [ex.submit(_run, common + ["-c", os.path.join(CSRC, s), "-o", o], verbose) for s, o in zip(SOURCES, objs)]
+        remarks = [r for j in jobs for r in j.result()]
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, verbose)
+    _report_scratch(remarks)
     return LIB
 
 
