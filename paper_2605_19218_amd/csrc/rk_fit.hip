@@ -676,21 +676,22 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
 // per (b, h_kv), the whole T-step loop in one launch (the paper's four kernels
 // per iteration exist to cut dispatch count; here there is nothing to dispatch).
 // All arithmetic is fp64: the Gram matrix of C_q V has the squared condition of
-// C_q's leading block, which fp32 cannot factor reliably, and MI355X's fp64 vector
-// rate equals its fp32 rate for scalar FMAs.
+// C_q's leading block, which fp32 cannot factor reliably; the fp64 vector rate of
+// this part is half its fp32 rate, which does not matter at this size.
 //
 // LDS (doubles): W [128][ks] (the basis, row stride ks = k padded so that ks % 32 == 8:
 // eight consecutive rows then start 16 banks apart), G packed lower triangle
-// [k(k+1)/2], per-column pivots, sigma, a k-vector.
+// [k(k+1)/2], per-column pivots, sigma, a k-vector, the published pivot row (x2).
 //
 // One iteration:
 //   W <- diag(sigma) C diag(sigma) W   register-tiled: thread = 4 rows x RJ columns
 //                                      (columns 32 apart), C read from global/L2 as
 //                                      float4 broadcasts, in place via registers;
 //   G <- W^T W (lower, 2x2 blocks), rho = eps tr(G) / k added to the diagonal;
-//   right-looking elimination of the stacked matrix [G; W], one barrier per column:
-//   step j uses column j (final since step j-1) to update columns > j,
-//       G[a][b] -= G[a][j] G[b][j] / G[j][j],   W[i][b] -= W[i][j] G[b][j] / G[j][j];
+//   right-looking elimination of the stacked matrix [W; G], one barrier per column,
+//   with the rows held in registers (see elim_step): step j uses row j of G (final
+//   since step j-1) to update columns > j,
+//       G[a][b] -= G[a][j] G[j][b] / G[j][j],   W[i][b] -= W[i][j] G[j][b] / G[j][j];
 //   this is the Cholesky factorisation and the solve V L^{-T} at once, with the
 //   square roots deferred: V[i][j] = W[i][j] / sqrt(pivot_j) at the end.
 constexpr int SUB_THREADS = 1024;
