@@ -500,61 +500,68 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
 
-    const int L = min(max(seq_len[b], 0), cap);
+    // ---- everything that does not need seq_len goes out first -----------------------------
+    // The sequence length costs a cold round trip to memory; the prologue operands (q, this
+    // thread's R_r pieces, delta_mu) and the first two tiles of every wave are requested before
+    // it is used.  The tile prefetch is speculative: it assumes the split is full and only
+    // checks that the tile lies inside the cache slab; rows past the real end are masked or
+    // skipped later (the prologue is on the kernel's critical path: while it runs only the
+    // prefetched tiles keep the memory system busy).
+    const int seq_raw = seq_len[b];
     // balanced partition of the 128-token tiles: the first (tiles % S) splits get one tile more
     const int tp = tiles_all / S, trem = tiles_all - tp * S;
     const int t0 = 128 * (split * tp + min(split, trem));
-    const int t1 = min(128 * ((split + 1) * tp + min(split + 1, trem)), L);
+    const int t1_full = 128 * ((split + 1) * tp + min(split + 1, trem));
+    const bf16_t* Ku = Kp + (size_t)u * cap * R;
+    const bf16_t* Vu = Vc + (size_t)u * cap * D;
+
+    constexpr int NPASS = (4 * R + 255) / 256;     // (channel quarter, column) items per thread
+    const float* Ru = Rr + (size_t)u * D * R;
+    uint4 qraw = make_uint4(0, 0, 0, 0);
+    {
+        const int hh = tid >> 4;
+        if (hh < Gc) qraw = *(const uint4*)(q + ((size_t)b * Hq + h0 + hh) * D + (tid & 15) * 8);
+    }
+    float xr[NPASS][32];
+#pragma unroll
+    for (int pss = 0; pss < NPASS; ++pss) {
+        const int idx = tid + 256 * pss;
+        const int cq = idx / R, j = idx - cq * R;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) xr[pss][c] = (idx < 4 * R) ? Ru[(32 * cq + c) * R + j] : 0.f;
+    }
+    float dmv = 0.f;
+    if (dmu && tid < D) dmv = dmu[(size_t)u * D + tid];
+
+    Tile TA, TB;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        TA.kt[tb] = (s16x4){0, 0, 0, 0};
+        TB.kt[tb] = (s16x4){0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < NFA; ++i) {
+            TA.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            TB.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        TA.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        TB.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    // this wave's tiles are wave, wave + 4, ...; tile k starts at tokA + 128 k
+    const int tokA = t0 + wave * 32;
+    const int t_spec = min(t1_full, cap);          // the slab ends at cap (a multiple of 32)
+    if (tokA + 32 <= t_spec) load_tile<R>(TA, Ku, Vu, tokA, lane);
+    if (tokA + 128 + 32 <= t_spec) load_tile<R>(TB, Ku, Vu, tokA + 128, lane);
+
+    const int L = min(max(seq_raw, 0), cap);
+    const int t1 = min(t1_full, L);
     const bool empty = t0 >= t1;
 
     if (!empty) {
-        const bf16_t* Ku = Kp + (size_t)u * cap * R;
-        const bf16_t* Vu = Vc + (size_t)u * cap * D;
         const int ntiles = (t1 - t0 + 31) >> 5;
-
-        // ---- prologue loads first: q (16 B per thread), this thread's R_r column pieces and
-        // delta_mu go out before anything else, so they are served by an idle memory system
-        // in ONE round trip instead of queueing behind the tile prefetches of every wave.
-        constexpr int NPASS = (4 * R + 255) / 256;     // (channel quarter, column) items per thread
-        const float* Ru = Rr + (size_t)u * D * R;
-        uint4 qraw = make_uint4(0, 0, 0, 0);
-        {
-            const int hh = tid >> 4;
-            if (hh < Gc) qraw = *(const uint4*)(q + ((size_t)b * Hq + h0 + hh) * D + (tid & 15) * 8);
-        }
-        float xr[NPASS][32];
-#pragma unroll
-        for (int pss = 0; pss < NPASS; ++pss) {
-            const int idx = tid + 256 * pss;
-            const int cq = idx / R, j = idx - cq * R;
-#pragma unroll
-            for (int c = 0; c < 32; ++c) xr[pss][c] = (idx < 4 * R) ? Ru[(32 * cq + c) * R + j] : 0.f;
-        }
-        float dmv = 0.f;
-        if (dmu && tid < D) dmv = dmu[(size_t)u * D + tid];
-
-        // then two tiles of K~/V per wave, in flight while q~ is computed
-        Tile TA, TB;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            TA.kt[tb] = (s16x4){0, 0, 0, 0};
-            TB.kt[tb] = (s16x4){0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < NFA; ++i) {
-                TA.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-                TB.kf[tb][i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-            }
-        }
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
-            TA.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-            TB.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-        }
-        // this wave's tiles are wave, wave + 4, ...: nk of them; tile k starts at tokA + 128 k
         const int nk = (ntiles - wave + 3) >> 2;
-        const int tokA = t0 + wave * 32;
-        if (nk > 0) load_tile<R>(TA, Ku, Vu, tokA, lane);
-        if (nk > 1) load_tile<R>(TB, Ku, Vu, tokA + 128, lane);
 
         // ---- q~ = q R_r scaled into the log2 domain, and the bias ----------------------
         {
