@@ -481,12 +481,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     constexpr int NF = Tile::NF, NFA = Tile::NFA;
     constexpr bool TAIL = Tile::TAIL;
 
-    // big: q~ partial sums [4][16][R] in the prologue, the four waves' O [4][16][128] at the end
+    // big: the four waves' O [4][16][128] at the end
     __shared__ __attribute__((aligned(16))) float big[4 * 16 * D];
-    __shared__ float qs[16][D];
-    __shared__ float qt[16][R];
+    __shared__ __attribute__((aligned(16))) float qt[16][R];
     __shared__ float sbias[16];
-    __shared__ float sdm[D];
+    __shared__ __attribute__((aligned(16))) float sdm[D];
     __shared__ float sm_m[4][16], sm_l[4][16];
 
     const bool direct = out != nullptr;     // the only split of a single-path call writes the result itself
@@ -515,22 +514,31 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* Ku = Kp + (size_t)u * cap * R;
     const bf16_t* Vu = Vc + (size_t)u * cap * D;
 
-    constexpr int NPASS = (4 * R + 255) / 256;     // (channel quarter, column) items per thread
+    // prologue operands, in matrix-core layout (lane (g, n)):
+    //   qfrag[i]     B operand: q of head n, channels 32 i + 8 g ..+7 (q is bf16: exact);
+    //   ra[bw][i][.] A operand: R_r^T block jb = wave + 4 bw: column 16 jb + n of R_r, the same
+    //                channels (fp32, split into a bf16 head + remainder pair before use);
+    constexpr int NJB = R / 16;                    // 16-column blocks of R_r
+    constexpr int NBW = (NJB + 3) / 4;             // blocks per wave
     const float* Ru = Rr + (size_t)u * D * R;
-    uint4 qraw = make_uint4(0, 0, 0, 0);
+    bf16x8 qfrag[4];
+    float ra[NBW][4][8];
     {
-        const int hh = tid >> 4;
-        if (hh < Gc) qraw = *(const uint4*)(q + ((size_t)b * Hq + h0 + hh) * D + (tid & 15) * 8);
-    }
-    float xr[NPASS][32];
+        const bf16_t* qrow = q + ((size_t)b * Hq + h0 + n) * D + 8 * g;
 #pragma unroll
-    for (int pss = 0; pss < NPASS; ++pss) {
-        const int idx = tid + 256 * pss;
-        const int cq = idx / R, j = idx - cq * R;
+        for (int i = 0; i < 4; ++i)
+            qfrag[i] = n < Gc ? *(const bf16x8*)(qrow + 32 * i) : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < 32; ++c) xr[pss][c] = (idx < 4 * R) ? Ru[(32 * cq + c) * R + j] : 0.f;
+        for (int bw = 0; bw < NBW; ++bw) {
+            const int jb = wave + 4 * bw;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj)
+                    ra[bw][i][jj] = jb < NJB ? Ru[(32 * i + 8 * g + jj) * R + 16 * jb + n] : 0.f;
+        }
     }
-    float dmv = 0.f;
+    float dmv = 0.f;                               // delta_mu goes through LDS (one value per thread)
     if (dmu && tid < D) dmv = dmu[(size_t)u * D + tid];
 
     Tile TA, TB;
@@ -564,48 +572,49 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         const int nk = (ntiles - wave + 3) >> 2;
 
         // ---- q~ = q R_r scaled into the log2 domain, and the bias ----------------------
+        // On the matrix cores: D[j][h] = sum_c R_r[c][j] q[h][c], one 16-column block of R_r per
+        // wave and pass, R_r as bf16 head + remainder (two MFMAs per 32 channels).  Lane (g, n)
+        // ends up with q~[head n][16 jb + 4 g + 0..3]: one 16-byte store to LDS, one barrier.
         {
-            const int hh = tid >> 4, c0 = (tid & 15) * 8;
-            const uint32_t w[4] = {qraw.x, qraw.y, qraw.z, qraw.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                qs[hh][c0 + 2 * e] = __uint_as_float(w[e] << 16);
-                qs[hh][c0 + 2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-            }
             if (tid < D) sdm[tid] = dmv;
-        }
-        __syncthreads();
-        // item (cq, j): partial sums over channels [32 cq, 32 cq + 32) for every head
 #pragma unroll
-        for (int pss = 0; pss < NPASS; ++pss) {
-            const int idx = tid + 256 * pss;
-            if (idx < 4 * R) {
-                const int cq = idx / R, j = idx - cq * R;
-                for (int hh = 0; hh < 16; ++hh) {
-                    float a = 0.f;
-                    if (hh < Gc) {
+            for (int bw = 0; bw < NBW; ++bw) {
+                const int jb = wave + 4 * bw;
+                if (jb < NJB) {
+                    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int c = 0; c < 32; ++c) a = fmaf(qs[hh][32 * cq + c], xr[pss][c], a);
+                    for (int i = 0; i < 4; ++i) {
+                        bf16x8 ah, al;
+#pragma unroll
+                        for (int jj = 0; jj < 8; ++jj) {
+                            __bf16 hi, lo;
+                            split_bf16(ra[bw][i][jj], hi, lo);
+                            ah[jj] = hi;
+                            al[jj] = lo;
+                        }
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, qfrag[i], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, qfrag[i], acc, 0, 0, 0);
                     }
-                    big[(cq * 16 + hh) * R + j] = a;
+                    *(f32x4*)&qt[n][16 * jb + 4 * g] = acc * scale_log2;
                 }
             }
         }
-        if (tid < 16) {
-            float a = 0.f;
-            if (tid < Gc) {
-                for (int c = 0; c < D; ++c) a = fmaf(qs[tid][c], sdm[c], a);
+        __syncthreads();
+        if (wave == 0) {                           // bias b_n = q_n . delta_mu, needed only at the end
+            float bpart = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const f32x4 d0 = *(const f32x4*)&sdm[32 * i + 8 * g], d1 = *(const f32x4*)&sdm[32 * i + 8 * g + 4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    bpart = fmaf((float)qfrag[i][jj], d0[jj], bpart);
+                    bpart = fmaf((float)qfrag[i][jj + 4], d1[jj], bpart);
+                }
             }
-            sbias[tid] = a * scale_log2;
+            bpart += __shfl_xor(bpart, 16);
+            bpart += __shfl_xor(bpart, 32);
+            if (g == 0) sbias[n] = bpart * scale_log2;
         }
-        __syncthreads();
-        for (int idx = tid; idx < 16 * R; idx += 256) {
-            int hh = idx / R, j = idx - hh * R;
-            float a = (big[(0 * 16 + hh) * R + j] + big[(1 * 16 + hh) * R + j]) +
-                      (big[(2 * 16 + hh) * R + j] + big[(3 * 16 + hh) * R + j]);
-            qt[hh][j] = a * scale_log2;
-        }
-        __syncthreads();
 
         // B operands of the score MFMAs: q~ of head n, split into bf16 head + remainder
         bf16x8 qh[NFA], ql[NFA];
