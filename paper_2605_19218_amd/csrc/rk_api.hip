@@ -115,7 +115,7 @@ rk_status check_text(rk_ctx* ctx, const rk_text* t, bool need_len)
 }
 
 // N_s and the number of 128-token tiles they share (split s gets floor(tiles / N_s) tiles, the
-// first tiles % N_s splits one more)
+// last tiles % N_s splits one more)
 void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_out)
 {
     const int G = L->n_q_heads / L->n_kv_heads;

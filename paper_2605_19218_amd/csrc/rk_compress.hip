@@ -156,13 +156,13 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
                     pk.y = pack2_bf16(acc[tt][2 * i][2], acc[tt][2 * i][3]);
                     pk.z = pack2_bf16(acc[tt][2 * i + 1][0], acc[tt][2 * i + 1][1]);
                     pk.w = pack2_bf16(acc[tt][2 * i + 1][2], acc[tt][2 * i + 1][3]);
-                    *(uint4*)(blk + (4 * i) * 128 + lane * 8) = pk;
+                    nt_store16(blk + (4 * i) * 128 + lane * 8, pk);
                 }
                 if (Cfg::TAIL) {
                     uint2 pk;
                     pk.x = pack2_bf16(acc[tt][Cfg::JB - 1][0], acc[tt][Cfg::JB - 1][1]);
                     pk.y = pack2_bf16(acc[tt][Cfg::JB - 1][2], acc[tt][Cfg::JB - 1][3]);
-                    *(uint2*)(blk + (4 * Cfg::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1)) = pk;
+                    nt_store8(blk + (4 * Cfg::NF + (g >> 1)) * 128 + n * 8 + 4 * (g & 1), pk);
                 }
             }
         }
@@ -209,7 +209,8 @@ __global__ __launch_bounds__(256) void v_retile(RowsDev rows, int Hkv, int cap, 
             int tl = jj < 4 ? 4 * g + jj : 16 + 4 * g + (jj - 4);
             x.v[jj] = tile[tl][c >> 3].v[c & 7];
         }
-        *(Oct<T>*)(Vu + (size_t)o * 8) = x;
+        if constexpr (sizeof(Oct<T>) == 16) nt_store16(Vu + (size_t)o * 8, __builtin_bit_cast(uint4, x));
+        else *(Oct<T>*)(Vu + (size_t)o * 8) = x;
     }
 }
 

@@ -38,10 +38,11 @@ __global__ __launch_bounds__(128) void decode_split_generic(
     const int G = Hq / Hkv, hk = hq / G, u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = min(max(seq_len[b], 0), cap);
-    // balanced partition of the 128-token tiles: the first (tiles % S) splits get one tile more
+    // balanced partition of the 128-token tiles: the LAST (tiles % S) splits get one tile more (the
+    // final tile of a cache is usually only partly filled, so the longer shares belong at the end)
     const int tp = tiles_all / S, trem = tiles_all - tp * S;
-    const int t0 = 128 * (split * tp + min(split, trem));
-    const int t1 = min(128 * ((split + 1) * tp + min(split + 1, trem)), L);
+    const int t0 = 128 * (split * tp + max(split - (S - trem), 0));
+    const int t1 = min(128 * ((split + 1) * tp + max(split + 1 - (S - trem), 0)), L);
     const size_t pidx = ((size_t)b * Hq + hq) * S + split;
     if (t0 >= t1) {
         if (tid == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
@@ -360,7 +361,7 @@ __device__ __forceinline__ void load_tile_k(DecTile<R>& T, const bf16_t* __restr
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
 #pragma unroll
-        for (int i = 0; i < DecTile<R>::NF; ++i) T.kf[tb][i] = *(const bf16x8*)(kb + tb * 16 * R + i * 512);
+        for (int i = 0; i < DecTile<R>::NF; ++i) T.kf[tb][i] = __builtin_nontemporal_load((const bf16x8*)(kb + tb * 16 * R + i * 512));
         if (DecTile<R>::TAIL) {
             const int g = lane >> 4, n = lane & 15;
             T.kt[tb] = *(const s16x4*)(Ku + (size_t)((tok0 >> 4) + tb) * (16 * R) +
@@ -374,7 +375,7 @@ __device__ __forceinline__ void load_tile_v(DecTile<R>& T, const bf16_t* __restr
 {
     const bf16_t* vb = Vu + (size_t)(tok0 >> 5) * 4096 + lane * 8;
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb) T.vf[cb] = *(const bf16x8*)(vb + cb * 512);
+    for (int cb = 0; cb < 8; ++cb) T.vf[cb] = __builtin_nontemporal_load((const bf16x8*)(vb + cb * 512));
 }
 
 template <int R>
@@ -507,10 +508,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     // skipped later (the prologue is on the kernel's critical path: while it runs only the
     // prefetched tiles keep the memory system busy).
     const int seq_raw = seq_len[b];
-    // balanced partition of the 128-token tiles: the first (tiles % S) splits get one tile more
+    // balanced partition of the 128-token tiles: the LAST (tiles % S) splits get one tile more (the
+    // final tile of a cache is usually only partly filled, so the longer shares belong at the end)
     const int tp = tiles_all / S, trem = tiles_all - tp * S;
-    const int t0 = 128 * (split * tp + min(split, trem));
-    const int t1_full = 128 * ((split + 1) * tp + min(split + 1, trem));
+    const int t0 = 128 * (split * tp + max(split - (S - trem), 0));
+    const int t1_full = 128 * ((split + 1) * tp + max(split + 1 - (S - trem), 0));
     const bf16_t* Ku = Kp + (size_t)u * cap * R;
     const bf16_t* Vu = Vc + (size_t)u * cap * D;
 

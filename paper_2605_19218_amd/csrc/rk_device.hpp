@@ -99,6 +99,17 @@ __host__ __device__ __forceinline__ size_t vidx(int t, int c) {
     return (size_t)(t >> 5) * 4096 + (size_t)(c >> 4) * 512 + (size_t)g * 128 + (size_t)(c & 15) * 8 + jj;
 }
 
+// 16-byte non-temporal (streaming) accesses: data that is written once and read once by a later
+// kernel, or read exactly once, should not displace anything in the caches
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void nt_store16(void* p, uint4 v) {
+    __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, (u32x4*)p);
+}
+__device__ __forceinline__ void nt_store8(void* p, uint2 v) {
+    __builtin_nontemporal_store((u32x2){v.x, v.y}, (u32x2*)p);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
