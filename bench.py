@@ -240,38 +240,89 @@ def main():
         NTOK = 16                                              # tokens generated per measurement (cap = L + 64)
         bound = L + 2 * NTOK + 2                               # host bound that covers warm-up, eager and replayed tokens
 
-        def token_step(stream=None):
+        def token_step(stream=None, fused=False):
             for i in range(NL):
                 st, ly = state[i], layers[i]
                 al = rk.Layout(B, Hq, Hkv, r_main, rk.RK_BF16, cap, bound - 1, seq_len=st["seq_len"])
                 dl = rk.Layout(B, Hq, Hkv, r_main, rk.RK_BF16, cap, bound, seq_len=st["seq_len"])
+                if fused:
+                    rk.rk_append_decode_attn(ctx, al, ly["k_new"], ly["v_new"], ly["q"], st["Rr"], st["dmu"], st["Kp"],
+                                             st["Vc"], st["seq_len"], 0.0, st["out"], dec_ws, stream=stream)
+                    continue
                 rk.rk_append(ctx, al, ly["k_new"], ly["v_new"], st["Rr"], st["Kp"], st["Vc"], st["seq_len"], stream=stream)
                 rk.rk_decode_attn(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], 0.0, st["out"], dec_ws,
                                   stream=stream)
-        for i in range(NL):
-            do_compress(r_main, state[i], layers[i])           # lengths back to L
-        token_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(NTOK):
-            token_step()
-        torch.cuda.synchronize()
-        eager_us = (time.perf_counter() - t0) * 1e6 / (NTOK * NL)
-        g = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        with torch.cuda.graph(g, stream=side):
-            token_step(stream=torch.cuda.current_stream())
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(NTOK - 1):
-            g.replay()
-        torch.cuda.synchronize()
-        graph_us = (time.perf_counter() - t0) * 1e6 / ((NTOK - 1) * NL)
-        assert int(state[0]["seq_len"][0]) == L + 2 * NTOK, "token loop lost count"
+
+        def time_loop(fused):
+            for i in range(NL):
+                do_compress(r_main, state[i], layers[i])           # lengths back to L
+            token_step(fused=fused)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(NTOK):
+                token_step(fused=fused)
+            torch.cuda.synchronize()
+            eager = (time.perf_counter() - t0) * 1e6 / (NTOK * NL)
+            g = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            with torch.cuda.graph(g, stream=side):
+                token_step(stream=torch.cuda.current_stream(), fused=fused)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(NTOK - 1):
+                g.replay()
+            torch.cuda.synchronize()
+            graph = (time.perf_counter() - t0) * 1e6 / ((NTOK - 1) * NL)
+            assert int(state[0]["seq_len"][0]) == L + 2 * NTOK, "token loop lost count"
+            del g
+            return eager, graph
+        eager_us, graph_us = time_loop(False)
+        fused_eager_us, fused_graph_us = time_loop(True)
         loop = dict(layers=NL, tokens=NTOK, eager_us_per_layer=eager_us, graph_us_per_layer=graph_us,
-                    note="wall clock per (rk_append + rk_decode_attn) of one layer, host launch overhead included; "
-                         "graph = one captured token step (3 kernels x %d layers) replayed" % NL)
-        del g
+                    fused_eager_us_per_layer=fused_eager_us, fused_graph_us_per_layer=fused_graph_us,
+                    note="wall clock per layer of one generated token, host launch overhead included: "
+                         "rk_append + rk_decode_attn (3 kernels) against rk_append_decode_attn (2 kernels); "
+                         "graph = one captured token step over the %d layers, replayed" % NL)
+
+    # ---- the paper's own decode loop: new tokens stay full-width in the text segment (Alg. 2 input K_pt) ----
+    if not args.no_sweep:
+        M0, CAP_T = 64, 128
+        tcfg = dict(cfg, id=cfg["id"] + 500, L=CAP_T)
+        tl = make_layer(tcfg, 0)
+        texts = [rk.Text(to_bf16(tl["K"]), to_bf16(tl["V"]), CAP_T - 1,
+                         torch.full((B,), M0, device=dev, dtype=torch.int32), capacity=CAP_T) for _ in range(NL)]
+        for i in range(NL):
+            do_compress(r_main, state[i], layers[i])               # lengths back to L
+
+        def text_step(fused):
+            for i in range(NL):
+                st, ly = state[i], layers[i]
+                _, dl = layouts(r_main, st)
+                if fused:
+                    rk.rk_append_text_decode_attn_dual(ctx, dl, ly["k_new"], ly["v_new"], ly["q"], st["Kp"], st["Vc"],
+                                                       st["Rr"], st["dmu"], texts[i], 0.0, st["out"], dec_ws)
+                    continue
+                rk.rk_append_text(ctx, dl, texts[i], ly["k_new"], ly["v_new"])
+                texts[i].max_len += 1                              # host bound after the append
+                rk.rk_decode_attn_dual(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], texts[i], 0.0,
+                                       st["out"], dec_ws)
+                texts[i].max_len -= 1
+        res = {}
+        for fused in (False, True):
+            for t in texts:
+                t.len.fill_(M0)
+            text_step(fused)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(NTOK):
+                text_step(fused)
+            torch.cuda.synchronize()
+            res[fused] = (time.perf_counter() - t0) * 1e6 / (NTOK * NL)
+            assert int(texts[0].len[0]) == M0 + NTOK + 1, "text loop lost count"
+        loop["dual_eager_us_per_layer"] = res[False]
+        loop["dual_fused_eager_us_per_layer"] = res[True]
+        loop["dual_note"] = ("rk_append_text + rk_decode_attn_dual (3 kernels) against "
+                             "rk_append_text_decode_attn_dual (2 kernels), text segment growing from %d rows" % M0)
 
     # ---- the paper's default solver (Alg. 1 steps 6-13) against the full eigendecomposition ----
     solvers = None

@@ -248,6 +248,28 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
                          const void* v_cache, const float* R_r, const float* delta_mu, float scale,
                          void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- rk_append followed by rk_decode_attn, fused ------------------------------
+ * One decode step of a layer whose new token joins the rotated cache (Sec. 3.2
+ * Step (1) then Alg. 2): row seq_len[b] of k_packed / v_cache receives
+ * k_new R_r / v_new, the softmax runs over seq_len[b] + 1 tokens (the new one
+ * included), and seq_len[b] += 1 on the device.  Results equal rk_append then
+ * rk_decode_attn up to fp32 rounding order (the stored row may differ from
+ * rk_append's by one unit in the last place of the storage type).  On the
+ * matrix-core path with H_q/H_kv < 16 the append rides in the
+ * decode's two launches (k_new takes a free column of the q~ = q R_r product);
+ * otherwise the call issues rk_append's and rk_decode_attn's launches.
+ * L->max_seq_len bounds seq_len[b] BEFORE the call; L->seq_len is ignored in
+ * favour of `seq_len` (device [B], read and written).  k_new, v_new: [B,H_kv,d],
+ * q, out: [B,H_q,d], all L->dtype; k_new 16-byte aligned.  Workspace:
+ * rk_decode_workspace_size of the layout with max_seq_len + 1.  A sequence
+ * already at capacity is left untouched and attends over what it has.
+ * Errors: INVALID_ARG, CAPACITY (max_seq_len + 1 > capacity; nothing is
+ * launched), UNSUPPORTED, WORKSPACE, HIP.                                      */
+rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new,
+                                const void* q, const float* R_r, const float* delta_mu, void* k_packed,
+                                void* v_cache, int32_t* seq_len, float scale, void* out, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 /* ---- Alg. 2 in full: steps 1-6 with the prompt/text segment (App. C phase 2) --
  * As rk_decode_attn for the visual segment; in addition the len[b] rows of
  * `text` are scored with the unrotated query, s_pt = q . K_pt * scale (no
@@ -273,6 +295,24 @@ rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, co
  * launched); on the device a sequence already at capacity is left untouched.  */
 rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, const void* k_new,
                          const void* v_new, void* stream);
+
+/* ---- rk_append_text followed by rk_decode_attn_dual, fused ---------------------
+ * One decode step of a layer whose new token joins the unrotated text segment
+ * (the paper's handling of tokens that arrive after prefill, Alg. 2 input
+ * K_pt): row len[b] of text->k / text->v receives k_new / v_new [B,H_kv,d],
+ * len[b] += 1 on the device, and the softmax of this step already includes the
+ * new row.  Same results as the two calls (the rows are copied, the attention
+ * arithmetic is the same code); the same two launches as rk_decode_attn_dual,
+ * the copy riding in the first.  text->len must be given; text->max_len bounds
+ * len[b] BEFORE the call.  k_new, v_new 16-byte aligned.  A sequence whose text
+ * segment is already full is left untouched and attends over what it has.
+ * Errors: as rk_decode_attn_dual, plus CAPACITY if text->max_len + 1 >
+ * text->capacity (nothing is launched).                                       */
+rk_status rk_append_text_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new,
+                                          const void* q, const void* k_packed, const void* v_cache,
+                                          const float* R_r, const float* delta_mu, const rk_text* text,
+                                          float scale, void* out, void* workspace, size_t workspace_bytes,
+                                          void* stream);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,8 @@ EXPORTS = [
     "rk_create", "rk_destroy", "rk_status_str", "rk_last_error", "rk_set_option", "rk_validate_layout",
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
-    "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace", "rk_query_sigma",
+    "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace", "rk_query_sigma", "rk_append_decode_attn",
+    "rk_append_text_decode_attn_dual",
 ]
 
 
@@ -100,6 +101,8 @@ def lib():
         L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
         L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
         L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
+        L.rk_append_text_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
+        L.rk_append_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
         L.rk_fit_subspace.argtypes = [vp, PL, PR, vp, u32, C.POINTER(rk_subspace), vp, vp, vp, vp, vp, vp, sz, vp]
         L.rk_query_sigma.argtypes = [vp, PL, vp, i64, i64, i64, i32, vp, vp]
         for name in EXPORTS:
@@ -276,6 +279,14 @@ def rk_append(ctx, layout: Layout, k_new, v_new, R_r, k_packed, v_cache, seq_len
                                 _ptr(v_cache), _ptr(seq_len), _stream(stream)))
 
 
+def rk_append_decode_attn(ctx, layout: Layout, k_new, v_new, q, R_r, delta_mu, k_packed, v_cache, seq_len,
+                          scale: float, out, workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    _check(ctx, lib().rk_append_decode_attn(ctx, C.byref(layout.c()), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(R_r),
+                                            _ptr(delta_mu), _ptr(k_packed), _ptr(v_cache), _ptr(seq_len),
+                                            float(scale), _ptr(out), _ptr(workspace), wb, _stream(stream)))
+
+
 def rk_decode_attn(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, scale: float, out, workspace,
                    stream=None, workspace_bytes: Optional[int] = None) -> None:
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
@@ -291,6 +302,17 @@ def rk_decode_attn_dual(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu
     _check(ctx, lib().rk_decode_attn_dual(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache),
                                           _ptr(R_r), _ptr(delta_mu), tref, float(scale), _ptr(out),
                                           _ptr(workspace), wb, _stream(stream)))
+
+
+def rk_append_text_decode_attn_dual(ctx, layout: Layout, k_new, v_new, q, k_packed, v_cache, R_r, delta_mu,
+                                    text: Text, scale: float, out, workspace, stream=None,
+                                    workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    tref = C.byref(text.c()) if text is not None else None
+    _check(ctx, lib().rk_append_text_decode_attn_dual(ctx, C.byref(layout.c()), _ptr(k_new), _ptr(v_new), _ptr(q),
+                                                      _ptr(k_packed), _ptr(v_cache), _ptr(R_r), _ptr(delta_mu), tref,
+                                                      float(scale), _ptr(out), _ptr(workspace), wb,
+                                                      _stream(stream)))
 
 
 def rk_append_text(ctx, layout: Layout, text: Text, k_new, v_new, stream=None) -> None:

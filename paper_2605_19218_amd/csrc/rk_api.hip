@@ -246,7 +246,8 @@ size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L)
     if (check_layout(nullptr, L) != RK_OK) return 0;
     int S, tiles;
     decode_plan(ctx, L, &S, &tiles);
-    return align_up((size_t)L->batch * L->n_q_heads * S * (D + 2) * sizeof(float), 256);
+    // (m, l, acc[d]) per split, plus one score per row for a fused append
+    return align_up((size_t)L->batch * L->n_q_heads * ((size_t)S * (D + 2) + 1) * sizeof(float), 256);
 }
 
 rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split)
@@ -470,9 +471,11 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
     return RK_OK;
 }
 
+// tk_new / tv_new non-null: one row per sequence joins the text segment inside the same launches
 static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
                                const void* v_cache, const float* R_r, const float* delta_mu, const rk_text* text,
-                               float scale, void* out, void* workspace, size_t workspace_bytes, void* stream)
+                               const void* tk_new, const void* tv_new, float scale, void* out, void* workspace,
+                               size_t workspace_bytes, void* stream)
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
     rk_status s = check_layout(ctx, L);
@@ -484,11 +487,22 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     if (L->max_seq_len > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "decode: max_seq_len %d exceeds capacity %d", L->max_seq_len, L->capacity);
     TextDev td{};
+    TextAppendDev ta{};
     if (text) {
-        s = check_text(ctx, text, false);
+        s = check_text(ctx, text, tk_new != nullptr);
         if (s != RK_OK) return s;
         if ((uintptr_t)q & 15) return fail(ctx, RK_ERR_INVALID_ARG, "decode (dual): q must be 16-byte aligned");
         td = TextDev{text->k, text->v, text->stride_b, text->stride_h, text->stride_t, text->len, text->max_len};
+        if (tk_new) {
+            if (!tv_new || ((uintptr_t)tk_new & 15) || ((uintptr_t)tv_new & 15))
+                return fail(ctx, RK_ERR_INVALID_ARG, "append_text_decode: k_new, v_new must be non-NULL, 16-byte aligned");
+            if (text->max_len + 1 > text->capacity)
+                return fail(ctx, RK_ERR_CAPACITY, "append_text_decode: %d + 1 rows exceed capacity %d", text->max_len,
+                            text->capacity);
+            td.max_len = text->max_len + 1;
+            ta = TextAppendDev{text->k, text->v, tk_new, tv_new, text->stride_b, text->stride_h, text->stride_t,
+                               text->len, text->capacity};
+        }
     }
     const size_t need = rk_decode_workspace_size(ctx, L);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
@@ -502,8 +516,8 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     decode_plan(ctx, L, &S, &tiles);
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
     e = launch_decode(L->dtype, use_mfma_decode(ctx, L), L->batch, L->n_q_heads, L->n_kv_heads, L->capacity,
-                      L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, sc,
-                      out, (float*)workspace, as_stream(stream));
+                      L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, nullptr,
+                      tk_new ? &ta : nullptr, sc, out, (float*)workspace, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }
@@ -512,8 +526,8 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
                          const void* v_cache, const float* R_r, const float* delta_mu, float scale, void* out,
                          void* workspace, size_t workspace_bytes, void* stream)
 {
-    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, nullptr, scale, out, workspace,
-                         workspace_bytes, stream);
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, nullptr, nullptr, nullptr, scale, out,
+                         workspace, workspace_bytes, stream);
 }
 
 rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
@@ -522,8 +536,69 @@ rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, co
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
     if (!text) return fail(ctx, RK_ERR_INVALID_ARG, "decode (dual): text is NULL");
-    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, text, scale, out, workspace,
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, text, nullptr, nullptr, scale, out, workspace,
                          workspace_bytes, stream);
+}
+
+rk_status rk_append_text_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new,
+                                          const void* q, const void* k_packed, const void* v_cache,
+                                          const float* R_r, const float* delta_mu, const rk_text* text, float scale,
+                                          void* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!text) return fail(ctx, RK_ERR_INVALID_ARG, "append_text_decode: text is NULL");
+    if (!k_new || !v_new) return fail(ctx, RK_ERR_INVALID_ARG, "append_text_decode: NULL pointer (k_new, v_new)");
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, text, k_new, v_new, scale, out, workspace,
+                         workspace_bytes, stream);
+}
+
+rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_new, const void* v_new, const void* q,
+                                const float* R_r, const float* delta_mu, void* k_packed, void* v_cache,
+                                int32_t* seq_len, float scale, void* out, void* workspace, size_t workspace_bytes,
+                                void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    rk_status s = check_layout(ctx, L);
+    if (s != RK_OK) return s;
+    if (!k_new || !v_new || !q || !R_r || !k_packed || !v_cache || !seq_len || !out)
+        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: NULL pointer");
+    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)k_new & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: caches and k_new must be 16-byte aligned");
+    if (L->max_seq_len + 1 > L->capacity)
+        return fail(ctx, RK_ERR_CAPACITY, "append_decode: %d + 1 rows exceed capacity %d", L->max_seq_len,
+                    L->capacity);
+    if (L->batch > APP_TICKETS) return fail(ctx, RK_ERR_UNSUPPORTED, "append_decode: batch too large");
+    // everything below is planned for the length after the append
+    rk_layout La = *L;
+    La.max_seq_len = L->max_seq_len + 1;
+    La.seq_len = seq_len;
+    const size_t need = rk_decode_workspace_size(ctx, &La);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
+        return fail(ctx, RK_ERR_WORKSPACE, "append_decode workspace: need %zu bytes, 16-byte aligned", need);
+    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    hipStream_t st = as_stream(stream);
+    int S, tiles;
+    decode_plan(ctx, &La, &S, &tiles);
+    const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
+    const bool mfma = use_mfma_decode(ctx, L);
+    const AppendDev app{k_new, v_new, seq_len};
+    const bool fused = decode_append_fusable(L->dtype, mfma, L->n_q_heads, L->n_kv_heads, L->keep);
+    if (!fused) {
+        // no free matrix-core column (G >= 16) or the plain kernels: the two steps run
+        // as the launches of rk_append and rk_decode_attn
+        e = launch_append(L->dtype, L->batch, L->n_kv_heads, L->capacity, L->keep, k_new, v_new, R_r, k_packed,
+                          v_cache, seq_len, ctx->tickets, st);
+        if (e != hipSuccess) return hip_fail(ctx, e, "append launch");
+    }
+    e = launch_decode(L->dtype, mfma, L->batch, L->n_q_heads, L->n_kv_heads, L->capacity, L->keep, S, tiles, q,
+                      k_packed, v_cache, R_r, delta_mu, seq_len, nullptr, fused ? &app : nullptr, nullptr, sc, out,
+                      (float*)workspace, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
+    return RK_OK;
 }
 
 rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, const void* k_new,

@@ -26,17 +26,38 @@ constexpr float NEG_INF = -__builtin_huge_valf();
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Fused text append: ONE wave per batch item copies the new Key/Value rows of all KV heads to
+// row len[b] of the text segment and bumps len[b].  Nothing else in the split kernel touches the
+// text segment or its length, and the merge kernel that reads them is ordered behind it.
+template <typename T>
+__device__ __forceinline__ void text_append_rows(const TextAppendDev& ta, int b, int Hkv, int lane)
+{
+    constexpr int PR = D * (int)sizeof(T) / 16;          // 16-byte pieces per row
+    const int len = ta.len[b];
+    if (len >= 0 && len < ta.capacity) {
+        for (int p = lane; p < Hkv * 2 * PR; p += 64) {
+            const int h = p / (2 * PR), rem = p - h * 2 * PR, isv = rem / PR, piece = rem - isv * PR;
+            const T* src = (const T*)(isv ? ta.v_new : ta.k_new) + ((size_t)b * Hkv + h) * D;
+            T* dst = (T*)(isv ? ta.v : ta.k) + (int64_t)b * ta.sb + (int64_t)h * ta.sh + (int64_t)len * ta.st;
+            ((uint4*)dst)[piece] = ((const uint4*)src)[piece];
+        }
+        if (lane == 0) ta.len[b] = len + 1;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Plain kernel: one block of 128 threads per (split, query head, batch item).
 template <typename T>
 __global__ __launch_bounds__(128) void decode_split_generic(
     const T* __restrict__ q, const T* __restrict__ Kp, const T* __restrict__ Vc, const float* __restrict__ Rr,
     const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
-    float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S)
+    float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S,
+    TextAppendDev ta)
 {
     const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int G = Hq / Hkv, hk = hq / G, u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (ta.k && split == 0 && hq == 0 && wave == 1) text_append_rows<T>(ta, b, Hkv, lane);
     const int L = min(max(seq_len[b], 0), cap);
     // balanced partition of the 128-token tiles: the LAST (tiles % S) splits get one tile more (the
     // final tile of a cache is usually only partly filled, so the longer shares belong at the end)
@@ -103,15 +124,31 @@ __global__ __launch_bounds__(128) void decode_split_generic(
 // Merge of the N_s partials (App. C phase 2, merge part): out = sum_i acc_i w_i / sum_i l_i w_i,
 // w_i = 2^(m_i - M).  An all-empty row (M = -inf) gives zeros.  One block per (b, h_q),
 // thread = channel; the loads of the S partials are independent and issued together.
+// With a fused append (ws_snew != NULL) the token appended by the split kernel enters as one
+// more term (m = its score, l = 1, acc = its Value row, read from v_new), and block (b, 0)
+// bumps seq_len[b]: no block of this kernel reads the length, and the next launch is ordered
+// behind this one.
 template <typename T>
 __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws_m, const float* __restrict__ ws_l,
-                                                    const float* __restrict__ ws_acc, int S, T* __restrict__ out)
+                                                    const float* __restrict__ ws_acc, int S, T* __restrict__ out,
+                                                    const float* __restrict__ ws_snew, const T* __restrict__ v_new,
+                                                    int Hq, int Hkv, int cap, int32_t* __restrict__ seq_len)
 {
     const size_t row = blockIdx.x;         // b * Hq + hq
     const int tid = threadIdx.x;
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
     const float* a = ws_acc + row * S * D + tid;
+    float sx = NEG_INF, vx = 0.f;
+    if (ws_snew) {
+        const int b = (int)(row / Hq), hq = (int)(row - (size_t)b * Hq);
+        sx = ws_snew[row];
+        vx = ld_elem(v_new + ((size_t)b * Hkv + hq / (Hq / Hkv)) * D + tid);
+        if (hq == 0 && tid == 0) {
+            const int len = seq_len[b];
+            if (len >= 0 && len < cap) seq_len[b] = len + 1;
+        }
+    }
     // online over chunks of 16 partials: the 48 loads of a chunk are independent of each other
     // and of the running maximum, so one memory round trip serves a whole chunk
     float M = NEG_INF, den = 0.f, num = 0.f;
@@ -139,6 +176,13 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
             }
             M = Mc;
         }
+    }
+    if (sx > NEG_INF) {                                 // the appended token
+        const float Mc = fmaxf(M, sx);
+        const float resc = exp2f(M - Mc), w = exp2f(sx - Mc);
+        den = fmaf(den, resc, w);
+        num = fmaf(num, resc, vx * w);
+        M = Mc;
     }
     const float o = (M > NEG_INF) ? num / den : 0.f;
     st_elem(out + row * D + tid, o);
@@ -471,12 +515,15 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
     }
 }
 
-template <int R>
+// STEP = false is the plain decode; STEP = true adds the fused appends of a whole decode step
+// (compiled separately so that the plain call carries none of their arguments or branches).
+template <int R, bool STEP>
 __global__ __launch_bounds__(256, 2) void decode_split_mfma(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vc,
-    const float* __restrict__ Rr, const float* __restrict__ dmu, const int32_t* __restrict__ seq_len, int Hq,
-    int Hkv, int cap, int tiles_all, float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l,
-    float* __restrict__ ws_acc, int S, bf16_t* __restrict__ out)
+    const bf16_t* __restrict__ q, bf16_t* Kp, bf16_t* Vc, const float* __restrict__ Rr,
+    const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int tiles_all,
+    float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S,
+    bf16_t* __restrict__ out, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+    float* __restrict__ ws_snew, TextAppendDev ta)
 {
     typedef DecTile<R> Tile;
     constexpr int NF = Tile::NF, NFA = Tile::NFA;
@@ -490,6 +537,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     __shared__ float sm_m[4][16], sm_l[4][16];
 
     const bool direct = out != nullptr;     // the only split of a single-path call writes the result itself
+    // Fused frozen-R append (k_new != NULL; the host guarantees G < 16 and never combines it
+    // with `direct`): k_new rides through the q~ MFMAs as column 15, which the query heads
+    // leave free, so k~_new = k_new R_r costs nothing.  Split 0 stores the new row
+    // (position seq_len[b], which no split of this launch scores: the length is bumped by the
+    // merge kernel) and hands the row's own score to the merge kernel.
+    const bool app = STEP && k_new != nullptr;
     const int G = Hq / Hkv;
     const int ngrp = (G + 15) >> 4;
     const int split = blockIdx.x, b = blockIdx.z;
@@ -499,6 +552,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
+    if (STEP && ta.k && split == 0 && blockIdx.y == 0 && wave == 3) text_append_rows<bf16_t>(ta, b, Hkv, lane);
 
     // ---- everything that does not need seq_len goes out first -----------------------------
     // The sequence length costs a cold round trip to memory; the prologue operands (q, this
@@ -526,10 +580,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     bf16x8 qfrag[4];
     float ra[NBW][4][8];
     {
-        const bf16_t* qrow = q + ((size_t)b * Hq + h0 + n) * D + 8 * g;
+        const bool newcol = app && n == 15;
+        const bf16_t* qrow = newcol ? k_new + (size_t)u * D + 8 * g : q + ((size_t)b * Hq + h0 + n) * D + 8 * g;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            qfrag[i] = n < Gc ? *(const bf16x8*)(qrow + 32 * i) : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            qfrag[i] = (n < Gc || newcol) ? *(const bf16x8*)(qrow + 32 * i) : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int bw = 0; bw < NBW; ++bw) {
             const int jb = wave + 4 * bw;
@@ -568,8 +623,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int L = min(max(seq_raw, 0), cap);
     const int t1 = min(t1_full, L);
     const bool empty = t0 >= t1;
+    const bool app_here = app && split == 0;       // this work-group stores and scores the new row
+    const bool app_ok = seq_raw >= 0 && seq_raw < cap;
 
-    if (!empty) {
+    if (!empty || app_here) {
         const int ntiles = (t1 - t0 + 31) >> 5;
         const int nk = (ntiles - wave + 3) >> 2;
 
@@ -597,7 +654,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
                         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, qfrag[i], acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, qfrag[i], acc, 0, 0, 0);
                     }
-                    *(f32x4*)&qt[n][16 * jb + 4 * g] = acc * scale_log2;
+                    *(f32x4*)&qt[n][16 * jb + 4 * g] = acc * ((app && n == 15) ? 1.f : scale_log2);
                 }
             }
         }
@@ -616,6 +673,29 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
             bpart += __shfl_xor(bpart, 16);
             bpart += __shfl_xor(bpart, 32);
             if (g == 0) sbias[n] = bpart * scale_log2;
+            if (app_here) {
+                // score of the new row against every head, with the row rounded to storage
+                // precision exactly as later steps will read it
+                float sp = 0.f;
+#pragma unroll
+                for (int jq = 0; jq < R / 16; ++jq) {
+                    const f32x4 a = *(const f32x4*)&qt[n][16 * jq + 4 * g], kx = *(const f32x4*)&qt[15][16 * jq + 4 * g];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sp = fmaf(a[e], bf16_to_f32(f32_to_bf16(kx[e])), sp);
+                }
+                sp += __shfl_xor(sp, 16);
+                sp += __shfl_xor(sp, 32);
+                if (g == 0 && n < Gc)
+                    ws_snew[(size_t)b * Hq + h0 + n] = app_ok ? fmaf(bpart, scale_log2, sp) : NEG_INF;
+            }
+        } else if (app_here && app_ok && grp == 0) {
+            if (wave == 1) {
+                for (int j = lane; j < R; j += 64)
+                    Kp[(size_t)u * cap * R + kidx(seq_raw, j, R)] = f32_to_bf16(qt[15][j]);
+            } else {
+                const int c = tid - 128;
+                Vc[(size_t)u * cap * D + vidx(seq_raw, c)] = v_new[(size_t)u * D + c];
+            }
         }
 
         // B operands of the score MFMAs: q~ of head n, split into bf16 head + remainder
@@ -748,34 +828,53 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r % 16 == 0 && r >= 16 && r <= 128; }
 
 template <int R>
-static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, const bf16_t* Kp, const bf16_t* Vc,
-                                 const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv,
-                                 int cap, int tiles_all, float sl2, float* m, float* l, float* acc, int S, bf16_t* out)
+static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf16_t* Kp, bf16_t* Vc, const float* Rr,
+                                 const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int tiles_all,
+                                 float sl2, float* m, float* l, float* acc, int S, bf16_t* out, const bf16_t* k_new,
+                                 const bf16_t* v_new, float* snew, const TextAppendDev& ta)
 {
-    hipLaunchKernelGGL(decode_split_mfma<R>, grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv, cap,
-                       tiles_all, sl2, m, l, acc, S, out);
+    if (k_new || ta.k)
+        hipLaunchKernelGGL((decode_split_mfma<R, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
+                           cap, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+    else
+        hipLaunchKernelGGL((decode_split_mfma<R, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
+                           cap, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+}
+
+// The fused append needs a free MFMA column next to the query heads: one group of fewer than 16.
+bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r)
+{
+    return mfma && decode_mfma_supported(dtype, r) && (Hq / Hkv) < 16;
 }
 
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
-                         const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
-                         hipStream_t st)
+                         const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
+                         float scale, void* out, float* ws, hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
     float* ws_m = ws;
     float* ws_l = ws_m + rows * S;
     float* ws_acc = ws_l + rows * S;
+    float* ws_snew = ws_acc + rows * S * D;            // [rows], fused append only
     const float sl2 = scale * 1.4426950408889634f;    // scores in the log2 domain
-    const bool direct = S == 1 && text == nullptr;    // a single split of a single-path call writes `out` itself
+    const bool direct = S == 1 && text == nullptr && app == nullptr;   // a lone split of a plain call writes `out` itself
     hipError_t e;
+    if (app && (text || !decode_append_fusable(dtype, mfma, Hq, Hkv, r))) return hipErrorInvalidValue;
+    if (tapp && !text) return hipErrorInvalidValue;
+    const TextAppendDev ta = tapp ? *tapp : TextAppendDev{};
     if (mfma && decode_mfma_supported(dtype, r)) {
         const int G = Hq / Hkv;
         dim3 grid(S, Hkv * ((G + 15) / 16), B);
-        const bf16_t *q_ = (const bf16_t*)q, *k_ = (const bf16_t*)Kp, *v_ = (const bf16_t*)Vc;
+        const bf16_t* q_ = (const bf16_t*)q;
+        // the caches are written only by a fused append, whose caller handed them over writable
+        bf16_t *k_ = const_cast<bf16_t*>((const bf16_t*)Kp), *v_ = const_cast<bf16_t*>((const bf16_t*)Vc);
+        const bf16_t* kn = app ? (const bf16_t*)app->k_new : nullptr;
+        const bf16_t* vn = app ? (const bf16_t*)app->v_new : nullptr;
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
         launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tiles_all, sl2, ws_m, ws_l, \
-                                 ws_acc, S, direct ? (bf16_t*)out : nullptr);                              \
+                                 ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta);         \
         break;
         switch (r) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
@@ -789,11 +888,11 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         if (dtype == 0)
             hipLaunchKernelGGL(decode_split_generic<float>, grid, dim3(128), 0, st, (const float*)q,
                                (const float*)Kp, (const float*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2,
-                               ws_m, ws_l, ws_acc, S);
+                               ws_m, ws_l, ws_acc, S, ta);
         else
             hipLaunchKernelGGL(decode_split_generic<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)q,
                                (const bf16_t*)Kp, (const bf16_t*)Vc, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2,
-                               ws_m, ws_l, ws_acc, S);
+                               ws_m, ws_l, ws_acc, S, ta);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -806,10 +905,13 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
                                (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out);
     } else if (dtype == 0) {
         hipLaunchKernelGGL(decode_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
-                           (float*)out);
+                           (float*)out, (const float*)nullptr, (const float*)nullptr, Hq, Hkv, cap,
+                           (int32_t*)nullptr);
     } else {
         hipLaunchKernelGGL(decode_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
-                           (bf16_t*)out);
+                           (bf16_t*)out, app ? (const float*)ws_snew : (const float*)nullptr,
+                           app ? (const bf16_t*)app->v_new : (const bf16_t*)nullptr, Hq, Hkv, cap,
+                           app ? app->seq_len : (int32_t*)nullptr);
     }
     return hipGetLastError();
 }

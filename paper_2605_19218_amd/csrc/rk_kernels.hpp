@@ -51,12 +51,35 @@ struct TextDev {
     const int32_t* len;      // device [B] or null (= max_len)
     int max_len;
 };
+// One token per sequence appended with the frozen R inside the decode launches (Sec. 3.2 Step (1)).
+struct AppendDev {
+    const void* k_new;       // [B, H_kv, d]
+    const void* v_new;       // [B, H_kv, d]
+    int32_t* seq_len;        // the same array the decode reads, writable: bumped by the merge kernel
+};
+// One full-width token per sequence appended to the text segment inside the split kernel.
+struct TextAppendDev {
+    void* k;                 // text segment (null = no append), strides as in TextDev
+    void* v;
+    const void* k_new;       // [B, H_kv, d]
+    const void* v_new;
+    int64_t sb, sh, st;
+    int32_t* len;            // device [B], bumped by the one wave that copies the rows
+    int capacity;
+};
+// whether launch_decode can take `app` for this shape (MFMA kernel with a free column: G < 16)
+bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r);
 // text == nullptr: visual segment only; otherwise the text segment joins the softmax in the merge kernel
+// app != nullptr: the new token is written to row seq_len[b] of both caches (which must then be writable),
+//                 joins the softmax, and seq_len[b] += 1; needs decode_append_fusable and text == nullptr
+// tapp != nullptr (needs text): row text.len[b] of the text segment receives k_new / v_new and the length is
+//                 bumped before the merge kernel reads it; text->max_len must already count the new row
 // tiles_all: 128-token tiles of the longest sequence; split s takes a balanced share of them
+// ws: partials, (S (d + 2) + 1) floats per (b, h_q)
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
-                         const int32_t* seq_len, const TextDev* text, float scale, void* out, float* ws,
-                         hipStream_t st);
+                         const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
+                         float scale, void* out, float* ws, hipStream_t st);
 hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,
                               void* kt, void* vt, int64_t sb, int64_t sh, int64_t st_, int32_t* len,
                               hipStream_t st);

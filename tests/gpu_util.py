@@ -105,6 +105,18 @@ class Pipeline:
         torch.cuda.synchronize()
         self.max_seq_len += 1
 
+    def append_decode(self, k_new, v_new, q_dev, use_bias=True, scale=0.0):
+        """The fused step: append with the frozen rotation, then attend over the longer cache."""
+        lay = self.layout()
+        after = rk.Layout(self.B, self.Hq, self.Hkv, self.r, rk_dtype(self.dtype), self.cap,
+                          min(self.max_seq_len + 1, self.cap), seq_len=self.seq_len)
+        ws = torch.empty(rk.rk_decode_workspace_size(self.ctx, after), device=DEV, dtype=torch.uint8)
+        rk.rk_append_decode_attn(self.ctx, lay, k_new, v_new, q_dev, self.Rr, self.dmu if use_bias else None,
+                                 self.Kp, self.Vc, self.seq_len, scale, self.out, ws)
+        torch.cuda.synchronize()
+        self.max_seq_len += 1
+        return to_host(self.out)
+
     def decode(self, q_dev, use_bias=True, scale=0.0):
         lay = self.layout()
         ws = torch.empty(rk.rk_decode_workspace_size(self.ctx, lay), device=DEV, dtype=torch.uint8)

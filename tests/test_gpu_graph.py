@@ -1,4 +1,5 @@
-"""The per-token serving loop (rk_append + rk_decode_attn for every layer) captured once into a
+"""The per-token serving loop (rk_append + rk_decode_attn for every layer, or the fused
+rk_append_decode_attn) captured once into a
 HIP graph and replayed: the entry points allocate nothing, clear nothing with memsets and take the
 caller's stream, so the caller's capture sees only kernel launches.  Every replay is checked
 bit for bit against the same calls made eagerly on a second, identically prefilled set of caches,
@@ -24,7 +25,8 @@ def ctx():
     rk.rk_destroy(c)
 
 
-def test_decode_loop_under_graph_replay(ctx):
+@pytest.mark.parametrize("fused", [False, True], ids=["two_calls", "fused_call"])
+def test_decode_loop_under_graph_replay(ctx, fused):
     dtype, B, Hq, Hkv, L, r, NLAY, NSTEP = "bf16", 2, 8, 2, 700, 64, 3, 5
     lengths = [700, 350]
     cap = L + NSTEP + 1
@@ -41,8 +43,12 @@ def test_decode_loop_under_graph_replay(ctx):
         for i, p in enumerate(pipes):
             # the host bound covers every replay: L + NSTEP tokens at most
             lay = rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, p.cap, L + NSTEP, seq_len=p.seq_len)
-            rk.rk_append(ctx, rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, p.cap, L + NSTEP - 1, seq_len=p.seq_len),
-                         kbuf[i], vbuf[i], p.Rr, p.Kp, p.Vc, p.seq_len, stream=stream)
+            before = rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, p.cap, L + NSTEP - 1, seq_len=p.seq_len)
+            if fused:
+                rk.rk_append_decode_attn(ctx, before, kbuf[i], vbuf[i], qbuf[i], p.Rr, p.dmu, p.Kp, p.Vc, p.seq_len,
+                                         0.0, p.out, ws[i], stream=stream)
+                continue
+            rk.rk_append(ctx, before, kbuf[i], vbuf[i], p.Rr, p.Kp, p.Vc, p.seq_len, stream=stream)
             rk.rk_decode_attn(ctx, lay, qbuf[i], p.Kp, p.Vc, p.Rr, p.dmu, 0.0, p.out, ws[i], stream=stream)
 
     lay0 = rk.Layout(B, Hq, Hkv, r, rk.RK_BF16, eager[0].cap, L + NSTEP, seq_len=eager[0].seq_len)
