@@ -172,6 +172,35 @@ def test_dual_decode_and_text_append_validation(ctx):
     assert app(None) == rk.RK_ERR_INVALID_ARG
 
 
+def test_fused_step_validation(ctx):
+    lay = layout()
+    ws = rk.rk_decode_workspace_size(ctx, layout(max_seq_len=1001))
+    # rk_append_decode_attn(ctx, L, k_new, v_new, q, R_r, delta_mu, k_packed, v_cache, seq_len, scale, out, ws)
+    step = lambda **kw: status_of(rk.rk_append_decode_attn, ctx, kw.get("lay", lay), kw.get("k", PTR), kw.get("v", PTR),
+                                  PTR, PTR, kw.get("dmu", PTR), PTR, PTR, kw.get("seq", PTR), 0.0, PTR, PTR,
+                                  workspace_bytes=kw.get("ws", ws))
+    assert step() == rk.RK_ERR_NO_DEVICE
+    assert step(dmu=None) == rk.RK_ERR_NO_DEVICE                  # the bias is optional
+    assert step(lay=layout(seq_len=None)) == rk.RK_ERR_NO_DEVICE  # the layout's seq_len is not used
+    assert step(seq=None) == rk.RK_ERR_INVALID_ARG
+    assert step(v=None) == rk.RK_ERR_INVALID_ARG
+    assert step(k=PTR + 2) == rk.RK_ERR_INVALID_ARG               # k_new feeds 16-byte loads
+    assert step(lay=layout(max_seq_len=1024)) == rk.RK_ERR_CAPACITY
+    assert step(ws=ws - 1) == rk.RK_ERR_WORKSPACE
+    # a workspace sized for the length after the append always suffices
+    assert rk.rk_decode_workspace_size(ctx, layout(max_seq_len=1001)) >= rk.rk_decode_workspace_size(ctx, lay)
+    ws = rk.rk_decode_workspace_size(ctx, lay)
+    dual = lambda t, **kw: status_of(rk.rk_append_text_decode_attn_dual, ctx, lay, kw.get("k", PTR), kw.get("v", PTR), PTR,
+                                     PTR, PTR, PTR, PTR, t, 0.0, PTR, PTR, workspace_bytes=kw.get("ws", ws))
+    assert dual(text(max_len=63)) == rk.RK_ERR_NO_DEVICE
+    assert dual(text()) == rk.RK_ERR_CAPACITY                     # 64 + 1 rows in a 64-row segment
+    assert dual(text(max_len=63, len=None)) == rk.RK_ERR_INVALID_ARG
+    assert dual(text(max_len=63), k=None) == rk.RK_ERR_INVALID_ARG
+    assert dual(text(max_len=63), v=PTR + 8) == rk.RK_ERR_INVALID_ARG
+    assert dual(None) == rk.RK_ERR_INVALID_ARG
+    assert dual(text(max_len=63), ws=ws - 1) == rk.RK_ERR_WORKSPACE
+
+
 def test_fit_subspace_validation(ctx):
     lay = layout()
     ws = rk.rk_fit_workspace_size(lay, 1000)
