@@ -237,3 +237,28 @@ def test_product_does_not_import_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "rotatek_oracle" not in text, f
+
+
+def test_c99_caller_builds_and_runs(tmp_path):
+    """The header is C (not C++) and the library links into a plain C program: a C99 caller
+    exercises the host-only entry points on a context without a device."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    root = ROOT
+    libdir = os.path.dirname(rk.LIB_PATH)
+    exe = str(tmp_path / "host_calls")
+    subprocess.run([cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c_abi", "host_calls.c"), "-o", exe, "-L", libdir, "-lrotatek",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    msg, n_splits, tokens, ws = res.stdout.strip().split("|")
+    assert "device" in msg and int(n_splits) >= 1 and int(tokens) % 128 == 0
+    c = rk.rk_create(rk.RK_DEVICE_NONE)
+    try:
+        assert int(ws) == rk.rk_decode_workspace_size(c, layout())
+    finally:
+        rk.rk_destroy(c)
