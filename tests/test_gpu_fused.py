@@ -86,6 +86,25 @@ def test_append_decode_fused(ctx, case):
         rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 0)
 
 
+def test_fused_full_size_gqa_16k(ctx):
+    """The benchmark configuration (B=8, 28 query / 4 KV heads, L=16384, r=64, bf16), the launch
+    configuration of bench.py's token loop: two fused steps, every output compared with the oracle."""
+    B, Hq, Hkv, L, r, dtype = 8, 28, 4, 16384, 64, "bf16"
+    data = layer(B, Hq, Hkv, L, dtype, 3)
+    p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, cap=L + 32)
+    p.max_seq_len = L
+    Rr = to_host(p.Rr)
+    for step in range(2):
+        new = layer(B, Hq, Hkv, 1, dtype, 6600 + step)
+        got = p.append_decode(to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype), to_dev(new["q"], dtype))
+        assert p.seq_len.cpu().tolist() == [L + step + 1] * B
+        Kt, Vc = p.unpacked()
+        for (b, h) in ((0, 0), (7, 3), (3, 1)):
+            check_packed(Kt[b, h, L + step:L + step + 1], new["k_new"][b, h][None].astype(np.float64), Rr[b, h], dtype)
+            assert np.array_equal(Vc[b, h, L + step], new["v_new"][b, h].astype(np.float64))
+        check_out(got, oracle_decode(p, new["q"], [L + step + 1] * B), dtype)
+
+
 def test_fused_new_token_matters(ctx):
     """Vacuity guard: a new Key aligned with the query must change the output visibly,
     i.e. the appended row really takes part in the softmax of its own step."""
