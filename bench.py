@@ -349,6 +349,43 @@ def main():
         solvers = dict(full_eigendecomposition_fit_us=stage_us["fit"]["mean"],
                        subspace_T5_fit_us=e0.elapsed_time(e1) * 1e3 / args.steps,
                        note="fit = covariance + solver; both in one rk_fit_* call, %d matrices of 128x128" % (B * Hkv))
+        # the same two solvers with one matrix per compute unit: all NL layers of the ring in ONE call
+        # (B * NL sequences of 1024 tokens each, so the covariance part stays small): a prefill that
+        # defers the fit to its end can batch layers like this, and one launch then keeps the whole
+        # chip busy instead of B * H_kv = 32 of its 256 compute units
+        UB, LB = B * NL, 1024
+        Kb = torch.stack([ly["K"][:, :, :LB] for ly in layers]).reshape(UB, Hkv, LB, D).contiguous()
+        lb = rk.Layout(UB, Hq, Hkv, r_main, rk.RK_BF16, LB, LB)
+        wsb = torch.empty(rk.rk_fit_workspace_size(lb, LB), device=dev, dtype=torch.uint8)
+        ob = dict(R=torch.empty(UB, Hkv, D, D, **f32), lam=torch.empty(UB, Hkv, D, **f32),
+                  mask=torch.empty(UB, Hkv, D, device=dev, dtype=torch.uint8),
+                  keep=torch.empty(UB, Hkv, r_main, device=dev, dtype=torch.int32),
+                  Rr=torch.empty(UB, Hkv, D, r_main, **f32), mu=torch.empty(UB, Hkv, D, **f32),
+                  dmu=torch.empty(UB, Hkv, D, **f32))
+        v0b = torch.randn(UB, Hkv, D, r_main, device=dev, dtype=torch.float32, generator=gen)
+        stb = torch.zeros(UB, Hkv, device=dev, dtype=torch.int32)
+
+        def fit_eig_batched():
+            out = rk.FitOut(ob["R"], ob["lam"], ob["mask"], ob["keep"], ob["Rr"], ob["mu"], ob["dmu"])
+            rk.rk_fit_rotation(ctx, lb, rk.Rows(Kb, LB), None, rk.RK_FIT_CENTER, out, wsb)
+
+        def fit_sub_batched():
+            rk.rk_fit_subspace(ctx, lb, rk.Rows(Kb, LB), None, rk.RK_FIT_CENTER, v0b, 5, 1e-6, ob["Rr"], ob["mu"],
+                               ob["dmu"], wsb, status=stb)
+        for name, fn in (("full_eigendecomposition", fit_eig_batched), ("subspace_T5", fit_sub_batched)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 4
+            solvers[name + "_batched"] = dict(matrices=UB * Hkv, tokens_per_matrix=LB, fit_us=us,
+                                              matrices_per_s=UB * Hkv / (us * 1e-6))
+        assert not stb.any().item(), "subspace iteration met a non-positive pivot (batched)"
+        del Kb, ob, wsb, v0b
         for i in range(NL):                                  # leave the ring as the eigen route made it
             do_fit(r_main, state[i], layers[i])
 
