@@ -25,7 +25,7 @@
  *     caller-allocated buffers of rk_cache_bytes() bytes whose INTERNAL layout is
  *     fragment-major (tiled so that the decode kernel's matrix-core operands are
  *     contiguous 1 KB pieces of HBM): per (b, h_kv) slab of `capacity` tokens,
- *       K~ element (token t, channel c):  [t/16][c/8][t%16][c%8], keep padded to 8
+ *       K~ element (token t, channel c):  [t/16][c/8][t%16][c%8], keep padded to 16
  *       V  element (token t, channel c):  [t/32][c/16][g][c%16][jj],
  *                                         g = (t%16)/4, jj = 4*((t%32)/16) + t%4
  *     Only rk_compress and rk_append write them; rk_unpack_cache converts a cache

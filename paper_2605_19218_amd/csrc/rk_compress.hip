@@ -32,16 +32,18 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
     __syncthreads();
     const float* Ru = Rr + (size_t)u * D * r;
     T* Ku = Kp + (size_t)u * cap * rp;
-    for (int o = tid; o < nt * r; o += 256) {
-        int t = o / r, j = o - t * r;
+    for (int o = tid; o < nt * rp; o += 256) {
+        int t = o / rp, j = o - t * rp;
         float a = 0.f;
-        for (int c = 0; c < D; ++c) a = fmaf(tile[t][c], Ru[c * r + j], a);
+        if (j < r)                                  // channels r .. rp - 1 are the layout's zero padding
+            for (int c = 0; c < D; ++c) a = fmaf(tile[t][c], Ru[c * r + j], a);
         st_elem(Ku + kidx(t0 + t, j, rp), a);
     }
 }
 
 // ---------------------------------------------------------------------------
-// MFMA kernel (bf16, r a multiple of 16).  Per wave: D^T[j, token] = R_r^T . K^T
+// MFMA kernel (bf16; R = r padded to a multiple of 16, columns r .. R - 1 of R_r read as
+// zero, which writes the layout's zero padding).  Per wave: D^T[j, token] = R_r^T . K^T
 // with v_mfma_f32_16x16x32_bf16; the B operand (lane (g, n): token n, channels
 // 32 i + 8 g ..+7) is a plain 16-byte load of a Key row, so Keys go from HBM
 // straight into MFMA registers.  R_r is split into bf16 head + remainder
@@ -70,7 +72,7 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
 }
 
 template <int R, bool GATHER>
-__global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int cap,
+__global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int cap, int r,
                                                      const float* __restrict__ Rr, bf16_t* __restrict__ Kp,
                                                      int32_t* __restrict__ seq_len_out)
 {
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
 
     // A fragments: block jb, k-step i, lane (gk, a): row a <-> output channel chan(jb, a);
     // k slots <-> input channels 32 i + 8 gk + jj.
-    const float* Ru = Rr + (size_t)u * D * R;
+    const float* Ru = Rr + (size_t)u * D * r;
     for (int f = tid; f < Cfg::JB * 4 * 64; f += 256) {
         int l = f & 63, i = (f >> 6) & 3, jb = f >> 8;
         int gk = l >> 4, a = l & 15;
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
         bf16x8 hi, lo;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
-            float x = Ru[(32 * i + 8 * gk + jj) * R + j];
+            float x = j < r ? Ru[(32 * i + 8 * gk + jj) * r + j] : 0.f;
             __bf16 xh, xl;
             split_bf16(x, xh, xl);
             hi[jj] = xh;
@@ -251,8 +253,8 @@ __global__ __launch_bounds__(256) void append_rows(int Hkv, int cap, int r, cons
             if (act) part[cq][j] = a;
         }
         __syncthreads();
-        if (tid < r) st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp),
-                             (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]));
+        if (tid < rp) st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp),        // zeros in the padding
+                              tid < r ? (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]) : 0.f);
         if (tid < D) Vc[(size_t)u * cap * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
     }
     __syncthreads();
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(256) void unpack_cache(int cap, int r, const T* __r
 
 // ---------------------------------------------------------------------------
 template <int R>
-static hipError_t launch_compress_mfma_r(const RowsDev& rows, int B, int Hkv, int cap, const float* Rr,
+static hipError_t launch_compress_mfma_r(const RowsDev& rows, int B, int Hkv, int cap, int r, const float* Rr,
                                          bf16_t* Kp, int32_t* seq_len_out, hipStream_t st)
 {
     typedef CompressCfg<R> Cfg;
@@ -299,27 +301,27 @@ static hipError_t launch_compress_mfma_r(const RowsDev& rows, int B, int Hkv, in
     if (nblk < 1) nblk = 1;
     if (rows.tok_idx)
         hipLaunchKernelGGL((compress_mfma<R, true>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
-                           cap, Rr, Kp, seq_len_out);
+                           cap, r, Rr, Kp, seq_len_out);
     else
         hipLaunchKernelGGL((compress_mfma<R, false>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
-                           cap, Rr, Kp, seq_len_out);
+                           cap, r, Rr, Kp, seq_len_out);
     return hipGetLastError();
 }
 
 hipError_t launch_compress(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int cap, int r,
                            const float* Rr, void* Kp, int32_t* seq_len_out, hipStream_t st)
 {
-    if (mfma && dtype == 1 && r % 16 == 0) {
+    if (mfma && dtype == 1) {
         bf16_t* kp = (bf16_t*)Kp;
-        switch (r) {
-            case 16: return launch_compress_mfma_r<16>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 32: return launch_compress_mfma_r<32>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 48: return launch_compress_mfma_r<48>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 64: return launch_compress_mfma_r<64>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 80: return launch_compress_mfma_r<80>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 96: return launch_compress_mfma_r<96>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 112: return launch_compress_mfma_r<112>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
-            case 128: return launch_compress_mfma_r<128>(rows, B, Hkv, cap, Rr, kp, seq_len_out, st);
+        switch (keep_padded(r)) {
+            case 16: return launch_compress_mfma_r<16>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 32: return launch_compress_mfma_r<32>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 48: return launch_compress_mfma_r<48>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 64: return launch_compress_mfma_r<64>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 80: return launch_compress_mfma_r<80>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 96: return launch_compress_mfma_r<96>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 112: return launch_compress_mfma_r<112>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
+            case 128: return launch_compress_mfma_r<128>(rows, B, Hkv, cap, r, Rr, kp, seq_len_out, st);
             default: break;
         }
     }

@@ -375,7 +375,8 @@ __global__ __launch_bounds__(128) void append_text_rows(const T* __restrict__ k_
 }
 
 // ---------------------------------------------------------------------------
-// MFMA split-K kernel (bf16 cache, r a multiple of 16).  256 threads = 4 waves;
+// MFMA split-K kernel (bf16 cache; R = r padded to a multiple of 16: the cache's padding
+// channels hold zeros and columns r .. R - 1 of R_r read as zero).  256 threads = 4 waves;
 // grid (split, H_kv * head groups of 16, B).  Each wave walks its own 32-token
 // tiles (tile index = wave, wave + 4, ...) with a private online-softmax state and
 // two tiles of loads in flight; the four states are merged through LDS at the end.
@@ -520,7 +521,7 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
 template <int R, bool STEP>
 __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* __restrict__ q, bf16_t* Kp, bf16_t* Vc, const float* __restrict__ Rr,
-    const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int tiles_all,
+    const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
     float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S,
     bf16_t* __restrict__ out, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
     float* __restrict__ ws_snew, TextAppendDev ta)
@@ -576,7 +577,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     //                channels (fp32, split into a bf16 head + remainder pair before use);
     constexpr int NJB = R / 16;                    // 16-column blocks of R_r
     constexpr int NBW = (NJB + 3) / 4;             // blocks per wave
-    const float* Ru = Rr + (size_t)u * D * R;
+    const float* Ru = Rr + (size_t)u * D * r;
     bf16x8 qfrag[4];
     float ra[NBW][4][8];
     {
@@ -592,7 +593,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj)
-                    ra[bw][i][jj] = jb < NJB ? Ru[(32 * i + 8 * g + jj) * R + 16 * jb + n] : 0.f;
+                    ra[bw][i][jj] = 16 * jb + n < r ? Ru[(32 * i + 8 * g + jj) * r + 16 * jb + n] : 0.f;
         }
     }
     float dmv = 0.f;                               // delta_mu goes through LDS (one value per thread)
@@ -825,20 +826,20 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 }
 
 // ---------------------------------------------------------------------------
-bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r % 16 == 0 && r >= 16 && r <= 128; }
+bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r >= 1 && r <= 128; }
 
 template <int R>
 static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf16_t* Kp, bf16_t* Vc, const float* Rr,
-                                 const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int tiles_all,
+                                 const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
                                  float sl2, float* m, float* l, float* acc, int S, bf16_t* out, const bf16_t* k_new,
                                  const bf16_t* v_new, float* snew, const TextAppendDev& ta)
 {
     if (k_new || ta.k)
         hipLaunchKernelGGL((decode_split_mfma<R, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
-                           cap, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+                           cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
     else
         hipLaunchKernelGGL((decode_split_mfma<R, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
-                           cap, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+                           cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
 }
 
 // The fused append needs a free MFMA column next to the query heads: one group of fewer than 16.
@@ -873,10 +874,10 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         const bf16_t* vn = app ? (const bf16_t*)app->v_new : nullptr;
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
-        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, tiles_all, sl2, ws_m, ws_l, \
+        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2, ws_m, ws_l, \
                                  ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta);         \
         break;
-        switch (r) {
+        switch (keep_padded(r)) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
             default: return hipErrorInvalidValue;
         }

@@ -79,7 +79,9 @@ __device__ __forceinline__ int64_t row_off(int64_t head_base, int64_t st, const 
 // 1 KB piece of HBM (lane l reads bytes [16 l, 16 l + 16)):
 //
 //  packed Keys K~: blocks of 16 tokens; inside a block channel octets are the
-//    slow axis:   [t / 16][c / 8][t % 16][c % 8]        (r padded to a multiple of 8)
+//    slow axis:   [t / 16][c / 8][t % 16][c % 8]        (r padded to a multiple of 16 with
+//    zero channels, so that every r runs on the 16-wide MFMA blocks; every writer of the
+//    cache stores the zeros)
 //    A 16x16x32 MFMA A-fragment of k-step i is octets 4i..4i+3 of a block:
 //    lane (g, n) holds token n, channels 32 i + 8 g ..+7.
 //
@@ -89,7 +91,7 @@ __device__ __forceinline__ int64_t row_off(int64_t head_base, int64_t st, const 
 //    MFMA hands the softmax weights of 32 tokens to lane group g, so P feeds the
 //    P.V MFMA as produced and lane (g, n) reads V's B-fragment for channel block
 //    cb as one 16-byte piece.
-__host__ __device__ __forceinline__ int keep_padded(int r) { return (r + 7) & ~7; }
+__host__ __device__ __forceinline__ int keep_padded(int r) { return (r + 15) & ~15; }
 __host__ __device__ __forceinline__ size_t kidx(int t, int c, int rp) {
     return (size_t)(t >> 4) * (16 * (size_t)rp) + (size_t)(c >> 3) * 128 + (size_t)(t & 15) * 8 + (c & 7);
 }

@@ -122,9 +122,9 @@ def test_compress_append_validation(ctx):
     assert status_of(rk.rk_unpack_cache, ctx, lay, PTR, PTR, PTR, PTR) == rk.RK_ERR_NO_DEVICE
     assert status_of(rk.rk_unpack_cache, ctx, lay, None, PTR, PTR, None) == rk.RK_ERR_INVALID_ARG
     assert status_of(rk.rk_unpack_cache, ctx, lay, PTR, PTR, None, None) == rk.RK_ERR_INVALID_ARG
-    # cache sizes: keep is padded to a multiple of 8 channels
+    # cache sizes: keep is padded to a multiple of 16 channels
     assert rk.rk_cache_bytes(lay) == (2 * 2 * 1024 * 64 * 2, 2 * 2 * 1024 * 128 * 2)
-    assert rk.rk_cache_bytes(layout(keep=37, dtype=rk.RK_F32))[0] == 2 * 2 * 1024 * 40 * 4
+    assert rk.rk_cache_bytes(layout(keep=37, dtype=rk.RK_F32))[0] == 2 * 2 * 1024 * 48 * 4
 
 
 def test_decode_plan_and_options(ctx):

@@ -38,6 +38,8 @@ FUSED_CASES = [
     ("mha_r16", "bf16", 2, 4, 4, 300, [300, 17], 16, 3, 0, False),
     ("gqa15_r128", "bf16", 1, 15, 1, 700, [700], 128, 3, 0, False),
     ("gqa4_r80", "bf16", 2, 8, 2, 640, [640, 127], 80, 4, 3, False),
+    ("gqa4_r56_padded", "bf16", 2, 8, 2, 640, [640, 127], 56, 4, 3, False),          # r padded to 64 in the cache
+    ("gqa7_r37_padded", "bf16", 1, 7, 1, 900, [900], 37, 3, 0, False),
     ("tile_edge", "bf16", 3, 4, 2, 256, [128, 256, 127], 32, 3, 0, False),       # new rows open a new tile
     ("from_empty", "bf16", 3, 4, 2, 40, [0, 1, 40], 32, 3, 0, False),
     ("g16_two_launch", "bf16", 1, 16, 1, 300, [300], 32, 3, 0, False),           # no free column: unfused launches

@@ -156,6 +156,9 @@ def test_eig_invariants_and_mask(ctx, with_sigma):
     ("bf16", 48, False, 333, [333, 70]), ("bf16", 16, False, 333, [333, 70]), ("bf16", 96, False, 333, [333, 70]),
     ("bf16", 128, False, 333, [333, 70]), ("bf16", 37, False, 333, [333, 70]),
     ("bf16", 80, False, 333, [333, 70]), ("bf16", 112, False, 333, [333, 70]),
+    # r not a multiple of 16: zero-padded channels, matrix-core kernel and plain kernel
+    ("bf16", 37, True, 333, [333, 70]), ("bf16", 56, False, 333, [333, 70]), ("bf16", 1, False, 333, [333, 70]),
+    ("bf16", 100, False, 2500, [2500, 1100]), ("bf16", 127, False, 333, [333, 70]), ("f32", 37, False, 333, [333, 70]),
     # several 256-token passes per work-group and a ragged end inside the last pass
     ("bf16", 64, False, 2500, [2500, 1100]), ("bf16", 48, False, 1300, [1300, 1025]),
 ])
@@ -175,6 +178,15 @@ def test_compress_parity(ctx, dtype, r, generic, L, lengths):
             check_packed(Kt[b, h, :n], data["K"][b, h, :n].astype(np.float64), Rr[b, h], dtype)
             assert np.array_equal(Vc[b, h, :n], data["V"][b, h, :n].astype(np.float64))
             assert not Kt[b, h, n:].any() and not Vc[b, h, n:].any()     # rows past n untouched
+    # the layout pads r to a multiple of 16 and every writer stores zeros there: [t/16][c/8][t%16][c%8]
+    rp = (r + 15) // 16 * 16
+    if rp > r:
+        raw = p.Kp.view(torch.float32 if dtype == "f32" else torch.bfloat16).float().cpu().numpy()
+        raw = raw.reshape(B, Hkv, p.cap // 16, rp // 8, 16, 8)
+        for b in range(B):
+            t = np.arange(lengths[b])
+            for c in range(r, rp):
+                assert not raw[b, :, t // 16, c // 8, t % 16, c % 8].any(), (b, c)
 
 
 def test_compress_token_list_and_strides(ctx):
@@ -219,7 +231,13 @@ DECODE_CASES = [
     ("r48", "bf16", 1, 8, 2, 700, None, 48, False, 0),
     ("r96", "bf16", 1, 8, 2, 700, None, 96, False, 0),
     ("r128_dense", "bf16", 1, 8, 2, 700, None, 128, False, 0),
+    # r that is not a multiple of 16: the cache pads it with zero channels, same matrix-core kernels
     ("r37_odd", "bf16", 1, 8, 2, 300, None, 37, False, 0),
+    ("r37_forced_generic", "bf16", 1, 8, 2, 300, None, 37, True, 0),
+    ("long_r37", "bf16", 1, 4, 4, 4096, None, 37, False, 2),
+    ("long_r56", "bf16", 2, 8, 2, 4096, [4096, 2999], 56, False, 2),
+    ("long_r100", "bf16", 1, 4, 4, 4096, None, 100, False, 2),
+    ("long_r127", "bf16", 1, 4, 4, 4096, None, 127, False, 2),
     ("g20_two_groups", "bf16", 1, 20, 1, 300, None, 32, False, 0),
     ("empty_and_one", "bf16", 3, 4, 2, 130, [0, 1, 130], 32, False, 0),
     ("one_split", "bf16", 2, 14, 2, 1000, [1000, 333], 64, False, 1),
@@ -238,9 +256,10 @@ DECODE_CASES = [
     ("g8_llama_like", "bf16", 1, 64, 8, 900, None, 64, False, 0),
     ("g16_full_block", "bf16", 2, 16, 1, 1500, [1500, 97], 32, False, 0),
     ("g32_two_blocks", "bf16", 1, 32, 1, 640, None, 64, False, 3),
-    # generic kernels at the ends of the range of r, both storage types
-    ("r1_generic", "bf16", 1, 4, 2, 300, None, 1, False, 0),
-    ("r8_generic", "bf16", 1, 4, 2, 300, None, 8, False, 0),
+    # the ends of the range of r, both storage types and both kernel families
+    ("r1", "bf16", 1, 4, 2, 300, None, 1, False, 0),
+    ("r8", "bf16", 1, 4, 2, 300, None, 8, False, 0),
+    ("r1_forced_generic", "bf16", 1, 4, 2, 300, None, 1, True, 0),
     ("r127_f32", "f32", 1, 2, 1, 257, None, 127, False, 0),
     ("r128_f32_dense", "f32", 1, 2, 2, 256, None, 128, False, 2),
     # lengths at tile and split edges
