@@ -232,31 +232,41 @@ __device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[4], const 
 // All loads of a pass (and, before the first pass, q and the first 16 visual
 // partials) are issued before anything waits, so a typical 64-token text segment
 // costs one memory round trip on top of the fold.
-template <typename T>
-__global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q, TextDev text, int Hq, int Hkv,
-                                                         float scale_log2, const float* __restrict__ ws_m,
-                                                         const float* __restrict__ ws_l,
-                                                         const float* __restrict__ ws_acc, int S,
-                                                         T* __restrict__ out)
+// THREADS = 128 serves the usual short segment; 512 (four times the tokens per pass at the same
+// work per thread) is launched for segments longer than 128 rows, where the passes, not the
+// launch, set the time.  The fold of the visual partials and the output use threads 0..127.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void decode_text_merge(const T* __restrict__ q, TextDev text, int Hq, int Hkv,
+                                                             float scale_log2, const float* __restrict__ ws_m,
+                                                             const float* __restrict__ ws_l,
+                                                             const float* __restrict__ ws_acc, int S,
+                                                             T* __restrict__ out, int n_pad)
 {
     constexpr int EPV = 16 / (int)sizeof(T);
     constexpr int CG = D / EPV;                 // channel groups: 16 or 32
-    constexpr int TG = 128 / CG;                // token groups: 8 or 4
-    constexpr int CHUNK = 64;                   // text tokens per pass
+    constexpr int TG = THREADS / CG;            // token groups
+    constexpr int CHUNK = THREADS / 2;          // text tokens per pass
     constexpr int NV = CHUNK / TG;              // Value pieces per thread and pass
     constexpr int NKQ = (D / 2) / EPV;          // pieces of half a Key row
+    constexpr int NWV = THREADS / 64;           // waves
 
-    const size_t row = blockIdx.x;              // b * Hq + hq
-    const int b = (int)(row / Hq), hq = (int)(row % Hq), hk = hq / (Hq / Hkv);
+    // Block -> (b, h_q): the G query heads of a KV head read the same text rows, so their blocks get
+    // indices that agree modulo 8 (the hardware deals consecutive work-groups round-robin to the 8
+    // XCDs) and the rows are fetched from HBM once per XCD-local L2 instead of once per head.
+    const int G = Hq / Hkv, upad = (int)gridDim.x / G;             // KV heads of the batch, padded to 8
+    const int gi = (int)blockIdx.x / upad, u = (int)blockIdx.x - gi * upad;
+    if (u >= upad - n_pad) return;
+    const int b = u / Hkv, hk = u - b * Hkv, hq = hk * G + gi;
+    const size_t row = (size_t)b * Hq + hq;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ts = tid >> 1, half = tid & 1;
     const int cg = tid % CG, tg = tid / CG;
-    __shared__ float ps[CHUNK], red[4];
+    __shared__ float ps[CHUNK], red[2 * NWV];
     __shared__ float part[TG][D];
 
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
-    const float* a = ws_acc + row * S * D + tid;
+    const float* a = ws_acc + row * S * D + min(tid, D - 1);
     const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
     const T* Kt = (const T*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh;
     const T* Vt = (const T*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh;
@@ -273,16 +283,23 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
 #pragma unroll
     for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
 
-    for (int base = 0; base < Mt; base += CHUNK) {
-        uint4 kraw[NKQ], vraw[NV];
-        const int tok = base + ts;
-        const bool valid = tok < Mt;
-        const T* krow = Kt + (int64_t)min(tok, Mt - 1) * text.st + half * (D / 2);
+    // The loads of pass i + 1 are issued before pass i is computed (row indices are clamped to the
+    // last row, so the surplus loads of the final pass are harmless re-reads): a long text segment
+    // then costs its arithmetic, not one memory round trip per 64 tokens.
+    uint4 kraw[NKQ], vraw[NV];
+    auto load_pass = [&](int base, uint4 (&kr)[NKQ], uint4 (&vr)[NV]) {
+        const T* krow = Kt + (int64_t)min(base + ts, Mt - 1) * text.st + half * (D / 2);
 #pragma unroll
-        for (int i = 0; i < NKQ; ++i) kraw[i] = *(const uint4*)(krow + i * EPV);
+        for (int i = 0; i < NKQ; ++i) kr[i] = *(const uint4*)(krow + i * EPV);
 #pragma unroll
         for (int k = 0; k < NV; ++k)      // rows past the end are clamped; their weight is 0
-            vraw[k] = *(const uint4*)(Vt + (int64_t)min(base + tg + TG * k, Mt - 1) * text.st + cg * EPV);
+            vr[k] = *(const uint4*)(Vt + (int64_t)min(base + tg + TG * k, Mt - 1) * text.st + cg * EPV);
+    };
+    if (Mt > 0) load_pass(0, kraw, vraw);
+    for (int base = 0; base < Mt; base += CHUNK) {
+        uint4 knext[NKQ], vnext[NV];
+        load_pass(base + CHUNK, knext, vnext);
+        const bool valid = base + ts < Mt;
 
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
@@ -302,14 +319,20 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
         float mt = wave_max(s);
         if (lane == 0) red[wave] = mt;
         __syncthreads();
-        const float m_new = fmaxf(Mx, fmaxf(red[0], red[1]));     // finite: the pass holds >= 1 token
+        float mred = red[0];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) mred = fmaxf(mred, red[w]);
+        const float m_new = fmaxf(Mx, mred);                       // finite: the pass holds >= 1 token
         const float p = valid ? exp2f(s - m_new) : 0.f;
         if (half == 0) ps[ts] = p;
         float lsum = wave_sum(half == 0 ? p : 0.f);
-        if (lane == 0) red[2 + wave] = lsum;
+        if (lane == 0) red[NWV + wave] = lsum;
         __syncthreads();
         const float alpha = exp2f(Mx - m_new);                     // 0 on the first pass
-        den = den * alpha + (red[2] + red[3]);
+        float lred = red[NWV];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) lred += red[NWV + w];
+        den = den * alpha + lred;
 #pragma unroll
         for (int e = 0; e < EPV; ++e) acc[e] *= alpha;
 #pragma unroll
@@ -321,6 +344,10 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
             for (int e = 0; e < EPV; ++e) acc[e] = fmaf(w, vf[e], acc[e]);
         }
         Mx = m_new;
+#pragma unroll
+        for (int i = 0; i < NKQ; ++i) kraw[i] = knext[i];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) vraw[k] = vnext[k];
         __syncthreads();                                           // ps and red are rewritten by the next pass
     }
 #pragma unroll
@@ -328,7 +355,7 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
     __syncthreads();
     float num = 0.f;
 #pragma unroll
-    for (int k = 0; k < TG; ++k) num += part[k][tid];
+    for (int k = 0; k < TG; ++k) num += part[k][tid & (D - 1)];
 
     // fold the visual partials (same arithmetic as decode_merge, starting from the text state)
     for (int i0 = 0; i0 < S; i0 += 16) {
@@ -350,7 +377,7 @@ __global__ __launch_bounds__(128) void decode_text_merge(const T* __restrict__ q
         }
     }
     const float o = (Mx > NEG_INF) ? num / den : 0.f;
-    st_elem(out + row * D + tid, o);
+    if (tid < D) st_elem(out + row * D + tid, o);
 }
 
 // One token per sequence appended to the full-width text segment (the paper keeps
@@ -898,12 +925,18 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         if (e != hipSuccess) return e;
     }
     if (text) {
+        const int U = B * Hkv, upad = (U + 7) & ~7, n_pad = upad - U;
+        const unsigned tblocks = (unsigned)(upad * (Hq / Hkv));
+        const bool wide = text->max_len > 128;       // bf16 only: the fp32 form would not fit its registers
         if (dtype == 0)
-            hipLaunchKernelGGL(decode_text_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, (const float*)q,
-                               *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (float*)out);
+            hipLaunchKernelGGL((decode_text_merge<float, 128>), dim3(tblocks), dim3(128), 0, st, (const float*)q,
+                               *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (float*)out, n_pad);
+        else if (wide)
+            hipLaunchKernelGGL((decode_text_merge<bf16_t, 512>), dim3(tblocks), dim3(512), 0, st,
+                               (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out, n_pad);
         else
-            hipLaunchKernelGGL(decode_text_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st,
-                               (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out);
+            hipLaunchKernelGGL((decode_text_merge<bf16_t, 128>), dim3(tblocks), dim3(128), 0, st,
+                               (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out, n_pad);
     } else if (dtype == 0) {
         hipLaunchKernelGGL(decode_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
                            (float*)out, (const float*)nullptr, (const float*)nullptr, Hq, Hkv, cap,

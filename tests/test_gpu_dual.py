@@ -71,6 +71,10 @@ DUAL_CASES = [
     ("gqa7_generic", "bf16", 2, 14, 2, 1000, [1000, 333], 64, [64, 5], 80, True, 0, D),
     ("text_spans_chunks", "bf16", 1, 8, 2, 700, None, 32, [300], 320, False, 0, D),
     ("padded_rows", "bf16", 2, 4, 2, 300, None, 48, [17, 129], 136, False, 0, D + 8),
+    # long segments: the 512-thread form of the text kernel (bf16, more than 128 rows), several passes, a batch
+    # whose KV-head count (6) is padded to 8 in the block map; fp32 keeps the 128-thread form at any length
+    ("wide_text_ragged", "bf16", 3, 14, 2, 600, [600, 100, 0], 64, [700, 1, 513], 704, False, 0, D),
+    ("f32_long_text", "f32", 1, 2, 1, 200, None, 16, [200], 200, False, 0, D),
     ("one_split", "bf16", 2, 14, 2, 120, [120, 64], 64, [9, 9], 16, False, 1, D),
     ("empty_segments", "bf16", 4, 4, 2, 130, [0, 0, 130, 77], 32, [0, 12, 0, 3], 16, False, 0, D),
     ("r37_odd_f32rows", "f32", 1, 4, 2, 300, None, 37, [40], 40, False, 0, D),
