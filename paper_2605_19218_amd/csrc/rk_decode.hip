@@ -193,9 +193,8 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
 // segment (Alg. 2 step 4: s_pt = q . K_pt / sqrt(d), no bias) followed by the fold
 // of the N_s visual partials; together they realise the single softmax over the
 // concatenated scores of Alg. 2 steps 5-6.  One block of 128 threads per (b, h_q).
-// The text segment is short (tens to a few hundred tokens), so it is handled with
-// plain vector code: thread = token for the scores (each lane reads its own 256- or
-// 512-byte Key row in 16-byte pieces), thread = channel for P.V (coalesced rows).
+// The text segment is short next to the visual cache (tens to a few hundred tokens),
+// so it is handled with plain vector code on coalesced row pieces.
 __device__ __forceinline__ void load_partials(const float* __restrict__ m, const float* __restrict__ l,
                                               const float* __restrict__ a, int i0, int S, float (&mv)[16],
                                               float (&lv)[16], float (&av)[16])
@@ -223,18 +222,34 @@ __device__ __forceinline__ void unpack16(const uint4& raw, float (&f)[4], const 
     f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
 }
 
-// Register mappings (EPV = elements per 16-byte piece: 8 for bf16, 4 for fp32):
-//   scores: thread (token tid / 2, half tid % 2) holds half a Key row and the matching
-//           half of q; the two halves meet in one lane exchange;
-//   P.V   : thread (channel group tid % CG, token group tid / CG) holds the 16-byte
-//           piece of every TG-th Value row of the pass; the TG partial sums meet in
-//           LDS once, after the last pass.
-// All loads of a pass (and, before the first pass, q and the first 16 visual
-// partials) are issued before anything waits, so a typical 64-token text segment
-// costs one memory round trip on top of the fold.
+// Sum over each aligned group of 16 lanes, left in all 16: quad swaps, then the two mirror
+// permutations of the data-parallel primitives (plain vector instructions, no LDS crossbar).
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_mov_f32<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+    v += dpp_mov_f32<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+    v += dpp_mov_f32<0x141>(v);     // row_half_mirror: lane i <-> 7 - i within 8
+    v += dpp_mov_f32<0x140>(v);     // row_mirror: lane i <-> 15 - i within 16
+    return v;
+}
+
+// Thread (cg, tg) = (16-byte piece of a row, token group): every pass it takes piece cg of the Key
+// and Value rows tg + TG k (k < 8), so a load instruction covers whole rows (the form "one thread
+// = half a Key row" read 16 bytes from each of 64 different cache lines per instruction and ran
+// at the L1 line rate, 4 us per 256 tokens).  The 8-channel partial dot products of a row meet
+// in its CG consecutive lanes by lane permutations, after which every lane of the row holds the
+// score; each thread then runs a private online softmax over its own tokens (the weights it
+// needs for P.V are the ones it has just computed), so a pass needs no LDS and no barrier.  The
+// TG thread-private states are folded through LDS once, after the last pass.  The loads of pass
+// i + 1 are issued before pass i is computed (row indices clamped to the last row).
 // THREADS = 128 serves the usual short segment; 512 (four times the tokens per pass at the same
-// work per thread) is launched for segments longer than 128 rows, where the passes, not the
-// launch, set the time.  The fold of the visual partials and the output use threads 0..127.
+// work per thread) is launched for bf16 segments longer than 128 rows.  The fold of the visual
+// partials and the output use threads 0..127.
 template <typename T, int THREADS>
 __global__ __launch_bounds__(THREADS) void decode_text_merge(const T* __restrict__ q, TextDev text, int Hq, int Hkv,
                                                              float scale_log2, const float* __restrict__ ws_m,
@@ -243,12 +258,10 @@ __global__ __launch_bounds__(THREADS) void decode_text_merge(const T* __restrict
                                                              T* __restrict__ out, int n_pad)
 {
     constexpr int EPV = 16 / (int)sizeof(T);
-    constexpr int CG = D / EPV;                 // channel groups: 16 or 32
+    constexpr int CG = D / EPV;                 // pieces per row = lanes per token: 16 or 32
     constexpr int TG = THREADS / CG;            // token groups
-    constexpr int CHUNK = THREADS / 2;          // text tokens per pass
-    constexpr int NV = CHUNK / TG;              // Value pieces per thread and pass
-    constexpr int NKQ = (D / 2) / EPV;          // pieces of half a Key row
-    constexpr int NWV = THREADS / 64;           // waves
+    constexpr int NV = 8;                       // rows per thread and pass
+    constexpr int CHUNK = TG * NV;              // text tokens per pass
 
     // Block -> (b, h_q): the G query heads of a KV head read the same text rows, so their blocks get
     // indices that agree modulo 8 (the hardware deals consecutive work-groups round-robin to the 8
@@ -258,104 +271,107 @@ __global__ __launch_bounds__(THREADS) void decode_text_merge(const T* __restrict
     if (u >= upad - n_pad) return;
     const int b = u / Hkv, hk = u - b * Hkv, hq = hk * G + gi;
     const size_t row = (size_t)b * Hq + hq;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ts = tid >> 1, half = tid & 1;
+    const int tid = threadIdx.x;
     const int cg = tid % CG, tg = tid / CG;
-    __shared__ float ps[CHUNK], red[2 * NWV];
+    __shared__ float sm_m[TG], sm_l[TG];
     __shared__ float part[TG][D];
 
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
     const float* a = ws_acc + row * S * D + min(tid, D - 1);
     const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
-    const T* Kt = (const T*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh;
-    const T* Vt = (const T*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh;
+    const T* Kt = (const T*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
+    const T* Vt = (const T*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
 
-    uint4 qraw[NKQ];
-#pragma unroll
-    for (int i = 0; i < NKQ; ++i) qraw[i] = *(const uint4*)(q + row * D + half * (D / 2) + i * EPV);
-
+    float qf[EPV];
+    {
+        const uint4 qraw = *(const uint4*)(q + row * D + cg * EPV);
+        unpack16(qraw, qf, (const T*)nullptr);
+    }
     float av[16], mv[16], lv[16];
     load_partials(m, l, a, 0, S, mv, lv, av);   // in flight during the text passes
 
-    float Mx = NEG_INF, den = 0.f;
+    float mrun = NEG_INF, lrun = 0.f;
     float acc[EPV];
 #pragma unroll
     for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
 
-    // The loads of pass i + 1 are issued before pass i is computed (row indices are clamped to the
-    // last row, so the surplus loads of the final pass are harmless re-reads): a long text segment
-    // then costs its arithmetic, not one memory round trip per 64 tokens.
-    uint4 kraw[NKQ], vraw[NV];
-    auto load_pass = [&](int base, uint4 (&kr)[NKQ], uint4 (&vr)[NV]) {
-        const T* krow = Kt + (int64_t)min(base + ts, Mt - 1) * text.st + half * (D / 2);
+    uint4 kraw[NV], vraw[NV];
+    auto load_pass = [&](int base, uint4 (&kr)[NV], uint4 (&vr)[NV]) {
 #pragma unroll
-        for (int i = 0; i < NKQ; ++i) kr[i] = *(const uint4*)(krow + i * EPV);
-#pragma unroll
-        for (int k = 0; k < NV; ++k)      // rows past the end are clamped; their weight is 0
-            vr[k] = *(const uint4*)(Vt + (int64_t)min(base + tg + TG * k, Mt - 1) * text.st + cg * EPV);
+        for (int k = 0; k < NV; ++k) {           // rows past the end are clamped; their weight is 0
+            const int64_t off = (int64_t)min(base + tg + TG * k, Mt - 1) * text.st;
+            kr[k] = *(const uint4*)(Kt + off);
+            vr[k] = *(const uint4*)(Vt + off);
+        }
     };
     if (Mt > 0) load_pass(0, kraw, vraw);
     for (int base = 0; base < Mt; base += CHUNK) {
-        uint4 knext[NKQ], vnext[NV];
+        uint4 knext[NV], vnext[NV];
         load_pass(base + CHUNK, knext, vnext);
-        const bool valid = base + ts < Mt;
 
-        float s0 = 0.f, s1 = 0.f;
+        float sc[NV];
 #pragma unroll
-        for (int i = 0; i < NKQ; ++i) {
-            float qf[EPV], kf[EPV];
-            unpack16(qraw[i], qf, (const T*)nullptr);
-            unpack16(kraw[i], kf, (const T*)nullptr);
+        for (int k = 0; k < NV; ++k) {
+            float kf[EPV];
+            unpack16(kraw[k], kf, (const T*)nullptr);
+            float d0 = 0.f, d1 = 0.f;
 #pragma unroll
             for (int e = 0; e < EPV; e += 2) {
-                s0 = fmaf(qf[e], kf[e], s0);
-                s1 = fmaf(qf[e + 1], kf[e + 1], s1);
+                d0 = fmaf(qf[e], kf[e], d0);
+                d1 = fmaf(qf[e + 1], kf[e + 1], d1);
             }
+            sc[k] = d0 + d1;
         }
-        float s = s0 + s1;
-        s += __shfl_xor(s, 1);
-        s = valid ? s * scale_log2 : NEG_INF;
-        float mt = wave_max(s);
-        if (lane == 0) red[wave] = mt;
-        __syncthreads();
-        float mred = red[0];
 #pragma unroll
-        for (int w = 1; w < NWV; ++w) mred = fmaxf(mred, red[w]);
-        const float m_new = fmaxf(Mx, mred);                       // finite: the pass holds >= 1 token
-        const float p = valid ? exp2f(s - m_new) : 0.f;
-        if (half == 0) ps[ts] = p;
-        float lsum = wave_sum(half == 0 ? p : 0.f);
-        if (lane == 0) red[NWV + wave] = lsum;
-        __syncthreads();
-        const float alpha = exp2f(Mx - m_new);                     // 0 on the first pass
-        float lred = red[NWV];
+        for (int k = 0; k < NV; ++k) {
+            sc[k] = row16_sum(sc[k]);
+            if (CG == 32) sc[k] += __shfl_xor(sc[k], 16);
+        }
+        float mloc = NEG_INF;
 #pragma unroll
-        for (int w = 1; w < NWV; ++w) lred += red[NWV + w];
-        den = den * alpha + lred;
+        for (int k = 0; k < NV; ++k) {
+            sc[k] = (base + tg + TG * k < Mt) ? sc[k] * scale_log2 : NEG_INF;
+            mloc = fmaxf(mloc, sc[k]);
+        }
+        const float m_new = fmaxf(mrun, mloc);
+        const float m_ref = (m_new > NEG_INF) ? m_new : 0.f;       // a token group may still be empty
+        const float alpha = exp2f(mrun - m_ref);                   // 0 while nothing has been seen
+        lrun *= alpha;
 #pragma unroll
         for (int e = 0; e < EPV; ++e) acc[e] *= alpha;
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const float w = ps[tg + TG * k];
+            const float w = exp2f(sc[k] - m_ref);                  // 0 for rows past the end
+            lrun += w;
             float vf[EPV];
             unpack16(vraw[k], vf, (const T*)nullptr);
 #pragma unroll
             for (int e = 0; e < EPV; ++e) acc[e] = fmaf(w, vf[e], acc[e]);
         }
-        Mx = m_new;
+        mrun = m_new;
 #pragma unroll
-        for (int i = 0; i < NKQ; ++i) kraw[i] = knext[i];
-#pragma unroll
-        for (int k = 0; k < NV; ++k) vraw[k] = vnext[k];
-        __syncthreads();                                           // ps and red are rewritten by the next pass
+        for (int k = 0; k < NV; ++k) {
+            kraw[k] = knext[k];
+            vraw[k] = vnext[k];
+        }
     }
+    // fold the TG thread-private states (all CG lanes of a token group hold the same m and l)
 #pragma unroll
     for (int e = 0; e < EPV; ++e) part[tg][cg * EPV + e] = acc[e];
+    if (cg == 0) { sm_m[tg] = mrun; sm_l[tg] = lrun; }
     __syncthreads();
-    float num = 0.f;
+    float Mx = NEG_INF, den = 0.f, num = 0.f;
 #pragma unroll
-    for (int k = 0; k < TG; ++k) num += part[k][tid & (D - 1)];
+    for (int k = 0; k < TG; ++k) Mx = fmaxf(Mx, sm_m[k]);
+    if (Mx > NEG_INF) {
+#pragma unroll
+        for (int k = 0; k < TG; ++k) {
+            const float w = exp2f(sm_m[k] - Mx);                   // 0 for an empty token group
+            den = fmaf(sm_l[k], w, den);
+            num = fmaf(part[k][tid & (D - 1)], w, num);
+        }
+    }
 
     // fold the visual partials (same arithmetic as decode_merge, starting from the text state)
     for (int i0 = 0; i0 < S; i0 += 16) {
