@@ -208,31 +208,35 @@ def main():
     # ---- dual-path decode (Alg. 2 steps 4-5): the same cache plus a 64-token full-width text segment ----
     dual = None
     if not args.no_sweep:
-        M = 64
-        tcfg = dict(cfg, id=cfg["id"] + 500, L=M)
-        tl = make_layer(tcfg, 0)
-        text = rk.Text(to_bf16(tl["K"]), to_bf16(tl["V"]), M,
-                       torch.full((B,), M, device=dev, dtype=torch.int32), capacity=M)
         for i in range(NL):
             do_compress(r_main, state[i], layers[i])       # reset lengths to L
+        by_len = {}
+        for M in (64, 1024):                               # a prompt-sized segment, and a long generated answer
+            tcfg = dict(cfg, id=cfg["id"] + 500, L=M)
+            tl = make_layer(tcfg, 0)
+            text = rk.Text(to_bf16(tl["K"]), to_bf16(tl["V"]), M,
+                           torch.full((B,), M, device=dev, dtype=torch.int32), capacity=M)
 
-        def do_dual(st, ly):
-            _, dl = layouts(r_main, st)
-            rk.rk_decode_attn_dual(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], text, 0.0,
-                                   st["out"], dec_ws)
-        for i in range(args.warmup):
-            do_dual(state[i % NL], layers[i % NL])
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(args.steps):
-            do_dual(state[i % NL], layers[i % NL])
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / args.steps
-        dbytes = decode_bytes(r_main, L) + B * Hkv * M * 2 * D * 2
-        dual = dict(text_tokens=M, us_per_step=us, GBps=dbytes / (us * 1e-6) / 1e9,
-                    single_path_us=sweep[str(r_main)]["us_per_step"])
+            def do_dual(st, ly):
+                _, dl = layouts(r_main, st)
+                rk.rk_decode_attn_dual(ctx, dl, ly["q"], st["Kp"], st["Vc"], st["Rr"], st["dmu"], text, 0.0,
+                                       st["out"], dec_ws)
+            for i in range(args.warmup):
+                do_dual(state[i % NL], layers[i % NL])
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                do_dual(state[i % NL], layers[i % NL])
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.steps
+            dbytes = decode_bytes(r_main, L) + B * Hkv * M * 2 * D * 2
+            by_len[M] = dict(us_per_step=us, GBps=dbytes / (us * 1e-6) / 1e9)
+            del text
+        dual = dict(text_tokens=64, us_per_step=by_len[64]["us_per_step"], GBps=by_len[64]["GBps"],
+                    single_path_us=sweep[str(r_main)]["us_per_step"],
+                    text_tokens_1024_us_per_step=by_len[1024]["us_per_step"])
 
     # ---- the per-token serving loop (append + decode on every layer of the ring), eager and as a HIP graph ----
     loop = None

@@ -4,6 +4,7 @@
 // rotation is fitted once at the end of prefill and reused, Sec. 3.2 Step (1)),
 // and the inverse re-tiling used to inspect a cache.
 #include "rk_kernels.hpp"
+#include <type_traits>
 
 namespace rk {
 
@@ -91,22 +92,30 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
     // A fragments: block jb, k-step i, lane (gk, a): row a <-> output channel chan(jb, a);
     // k slots <-> input channels 32 i + 8 gk + jj.
     const float* Ru = Rr + (size_t)u * D * r;
-    for (int f = tid; f < Cfg::JB * 4 * 64; f += 256) {
-        int l = f & 63, i = (f >> 6) & 3, jb = f >> 8;
-        int gk = l >> 4, a = l & 15;
-        int j = Cfg::chan(jb, a);
-        bf16x8 hi, lo;
+    // EXACT: r is the kernel's own width (the common case), so the row stride of R_r is a compile-time
+    // constant; otherwise r < R and the columns r .. R - 1 are the zero padding
+    auto build = [&](auto exact) {
+        constexpr bool EXACT = decltype(exact)::value;
+        const int rs = EXACT ? R : r;
+        for (int f = tid; f < Cfg::JB * 4 * 64; f += 256) {
+            int l = f & 63, i = (f >> 6) & 3, jb = f >> 8;
+            int gk = l >> 4, a = l & 15;
+            int j = Cfg::chan(jb, a);
+            bf16x8 hi, lo;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            float x = j < r ? Ru[(32 * i + 8 * gk + jj) * r + j] : 0.f;
-            __bf16 xh, xl;
-            split_bf16(x, xh, xl);
-            hi[jj] = xh;
-            lo[jj] = xl;
+            for (int jj = 0; jj < 8; ++jj) {
+                float x = (EXACT || j < r) ? Ru[(32 * i + 8 * gk + jj) * rs + j] : 0.f;
+                __bf16 xh, xl;
+                split_bf16(x, xh, xl);
+                hi[jj] = xh;
+                lo[jj] = xl;
+            }
+            frag[((jb * 4 + i) * 2 + 0) * 64 + l] = hi;
+            frag[((jb * 4 + i) * 2 + 1) * 64 + l] = lo;
         }
-        frag[((jb * 4 + i) * 2 + 0) * 64 + l] = hi;
-        frag[((jb * 4 + i) * 2 + 1) * 64 + l] = lo;
-    }
+    };
+    if (r == R) build(std::true_type{});
+    else build(std::false_type{});
     __syncthreads();
 
     const bf16_t* base = (const bf16_t*)rows.data;
