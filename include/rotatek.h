@@ -276,10 +276,12 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
  * bias), and ONE softmax runs over the concatenation [s_vis; s_pt]; out =
  * P [V_vis; V_pt].  The bias therefore matters here: it shifts the visual
  * scores against the text scores.  Either segment may be empty per sequence;
- * both empty yields zeros.  Always two launches: the split-K kernel over the
- * visual cache, then one kernel that runs the text attention and folds the
- * visual partials (the fusion App. C describes).  Same workspace as
- * rk_decode_attn.
+ * both empty yields zeros.  Always two launches.  On the matrix-core path the
+ * text attention runs in extra work-groups of the split-K launch, in slices of
+ * about 512 rows that each leave a partial of their own, and the merge kernel
+ * folds visual and text partials alike; with fp32 storage or the plain kernels
+ * the second kernel runs the text attention itself and then folds the visual
+ * partials (the fusion App. C describes).  Same workspace as rk_decode_attn.
  * Errors: as rk_decode_attn, plus INVALID_ARG for a malformed `text`
  * (NULL pointers, misaligned base or strides, max_len > capacity).            */
 rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,

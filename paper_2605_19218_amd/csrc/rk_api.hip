@@ -246,8 +246,8 @@ size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L)
     if (check_layout(nullptr, L) != RK_OK) return 0;
     int S, tiles;
     decode_plan(ctx, L, &S, &tiles);
-    // (m, l, acc[d]) per split, plus one score per row for a fused append
-    return align_up((size_t)L->batch * L->n_q_heads * ((size_t)S * (D + 2) + 1) * sizeof(float), 256);
+    // (m, l, acc[d]) per split and per text slice of the dual path, plus one score per row for a fused append
+    return align_up((size_t)L->batch * L->n_q_heads * ((size_t)(S + DECODE_TEXT_SLICES_MAX) * (D + 2) + 1) * sizeof(float), 256);
 }
 
 rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split)

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(128) void decode_split_generic(
 // more term (m = its score, l = 1, acc = its Value row, read from v_new), and block (b, 0)
 // bumps seq_len[b]: no block of this kernel reads the length, and the next launch is ordered
 // behind this one.
-template <typename T>
+template <typename T, int MC>
 __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws_m, const float* __restrict__ ws_l,
                                                     const float* __restrict__ ws_acc, int S, T* __restrict__ out,
                                                     const float* __restrict__ ws_snew, const T* __restrict__ v_new,
@@ -149,13 +149,14 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
             if (len >= 0 && len < cap) seq_len[b] = len + 1;
         }
     }
-    // online over chunks of 16 partials: the 48 loads of a chunk are independent of each other
-    // and of the running maximum, so one memory round trip serves a whole chunk
+    // online over chunks of MC partials: the 3 MC loads of a chunk are independent of each other
+    // and of the running maximum, so one memory round trip serves a whole chunk (MC = 16; 24 when
+    // text slices of the dual path sit behind the splits)
     float M = NEG_INF, den = 0.f, num = 0.f;
-    for (int i0 = 0; i0 < S; i0 += 16) {
-        float av[16], mv[16], lv[16];
+    for (int i0 = 0; i0 < S; i0 += MC) {
+        float av[MC], mv[MC], lv[MC];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < MC; ++k) {
             const bool in = i0 + k < S;
             av[k] = in ? a[(size_t)(i0 + k) * D] : 0.f;
             mv[k] = in ? m[i0 + k] : NEG_INF;
@@ -163,13 +164,13 @@ __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws
         }
         float Mc = M;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) Mc = fmaxf(Mc, mv[k]);
+        for (int k = 0; k < MC; ++k) Mc = fmaxf(Mc, mv[k]);
         if (Mc > NEG_INF) {
             const float resc = exp2f(M - Mc);           // 0 on the first non-empty chunk
             den *= resc;
             num *= resc;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
+            for (int k = 0; k < MC; ++k) {
                 float w = exp2f(mv[k] - Mc);            // 2^(-inf) = 0 for empty splits
                 den = fmaf(lv[k], w, den);
                 num = fmaf(av[k], w, num);
@@ -418,6 +419,115 @@ __global__ __launch_bounds__(128) void append_text_rows(const T* __restrict__ k_
 }
 
 // ---------------------------------------------------------------------------
+// One slice of the text attention as a split-K partial: the same thread mapping and
+// thread-private online softmax as decode_text_merge, run by a 256-thread work-group of the
+// split launch for one query head and rows [r0, r1) of the text segment; the result goes to a
+// workspace slot of its own as (m, l, acc) in the log2 domain, with no bias (Alg. 2 step 4), and
+// the plain merge kernel folds it with the visual partials.  `lds` needs 16 * 128 + 32 floats.
+__device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const TextDev& text, int b, int hk,
+                                             size_t row, int ts, int TS, float scale_log2,
+                                             float* __restrict__ ws_m, float* __restrict__ ws_l,
+                                             float* __restrict__ ws_acc, size_t pidx, float* lds)
+{
+    constexpr int EPV = 8, CG = 16, TG = 16, NV = 8, CHUNK = TG * NV;
+    const int tid = threadIdx.x;
+    const int cg = tid % CG, tg = tid / CG;
+    float (*part)[D] = (float (*)[D])lds;
+    float* sm_m = lds + TG * D;
+    float* sm_l = sm_m + TG;
+    const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
+    // slices of whole passes, the last one takes what is left
+    const int per = ((Mt + TS - 1) / TS + CHUNK - 1) / CHUNK * CHUNK;
+    const int r0 = ts * per, r1 = min(r0 + per, Mt);
+    const bf16_t* Kt = (const bf16_t*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
+    const bf16_t* Vt = (const bf16_t*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
+
+    float qf[EPV];
+    {
+        const uint4 qraw = *(const uint4*)(q + row * D + cg * EPV);
+        unpack16(qraw, qf, (const bf16_t*)nullptr);
+    }
+    float mrun = NEG_INF, lrun = 0.f;
+    float acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+
+    uint4 kraw[NV], vraw[NV];
+    auto load_pass = [&](int base, uint4 (&kr)[NV], uint4 (&vr)[NV]) {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {           // rows past the end are clamped; their weight is 0
+            const int64_t off = (int64_t)min(base + tg + TG * k, Mt - 1) * text.st;
+            kr[k] = *(const uint4*)(Kt + off);
+            vr[k] = *(const uint4*)(Vt + off);
+        }
+    };
+    if (r0 < r1) load_pass(r0, kraw, vraw);
+    for (int base = r0; base < r1; base += CHUNK) {
+        uint4 knext[NV], vnext[NV];
+        load_pass(base + CHUNK, knext, vnext);
+        float sc[NV];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float kf[EPV];
+            unpack16(kraw[k], kf, (const bf16_t*)nullptr);
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPV; e += 2) {
+                d0 = fmaf(qf[e], kf[e], d0);
+                d1 = fmaf(qf[e + 1], kf[e + 1], d1);
+            }
+            sc[k] = row16_sum(d0 + d1);
+        }
+        float mloc = NEG_INF;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            sc[k] = (base + tg + TG * k < r1) ? sc[k] * scale_log2 : NEG_INF;
+            mloc = fmaxf(mloc, sc[k]);
+        }
+        const float m_new = fmaxf(mrun, mloc);
+        const float m_ref = (m_new > NEG_INF) ? m_new : 0.f;       // a token group may still be empty
+        const float alpha = exp2f(mrun - m_ref);
+        lrun *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const float w = exp2f(sc[k] - m_ref);
+            lrun += w;
+            float vf[EPV];
+            unpack16(vraw[k], vf, (const bf16_t*)nullptr);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(w, vf[e], acc[e]);
+        }
+        mrun = m_new;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            kraw[k] = knext[k];
+            vraw[k] = vnext[k];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) part[tg][cg * EPV + e] = acc[e];
+    if (cg == 0) { sm_m[tg] = mrun; sm_l[tg] = lrun; }
+    __syncthreads();
+    if (tid < D) {
+        float Mx = NEG_INF, den = 0.f, num = 0.f;
+#pragma unroll
+        for (int k = 0; k < TG; ++k) Mx = fmaxf(Mx, sm_m[k]);
+        if (Mx > NEG_INF) {
+#pragma unroll
+            for (int k = 0; k < TG; ++k) {
+                const float w = exp2f(sm_m[k] - Mx);               // 0 for an empty token group
+                den = fmaf(sm_l[k], w, den);
+                num = fmaf(part[k][tid], w, num);
+            }
+        }
+        ws_acc[pidx * D + tid] = num;
+        if (tid == 0) { ws_m[pidx] = Mx; ws_l[pidx] = den; }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // MFMA split-K kernel (bf16 cache; R = r padded to a multiple of 16: the cache's padding
 // channels hold zeros and columns r .. R - 1 of R_r read as zero).  256 threads = 4 waves;
 // grid (split, H_kv * head groups of 16, B).  Each wave walks its own 32-token
@@ -559,15 +669,23 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
     }
 }
 
-// STEP = false is the plain decode; STEP = true adds the fused appends of a whole decode step
-// (compiled separately so that the plain call carries none of their arguments or branches).
-template <int R, bool STEP>
+// STEP = false is the plain decode; STEP = true adds the fused appends of a whole decode step;
+// TEXT = true adds work-groups that compute slices of the text attention (dual path) next to the
+// visual splits.  Each form is compiled separately, so the plain call carries none of the others'
+// arguments or branches.
+// Grid: (split, (h_kv, head group), b).  With TEXT the grid has one dimension: indices [0, n_vis)
+// are the visual splits in the same order (split fastest), and from n_vis rounded up to 8 on come
+// the text work-groups, in blocks of 8 (unit, slice) groups x Gm heads numbered 8 * head + group % 8:
+// the heads of a group, which read the same text rows, then have indices that agree modulo 8, i.e.
+// run on one XCD (work-groups are dealt round-robin to the 8 XCDs) at about the same time, and share
+// its L2.
+template <int R, bool STEP, bool TEXT>
 __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* __restrict__ q, bf16_t* Kp, bf16_t* Vc, const float* __restrict__ Rr,
     const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
     float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S,
     bf16_t* __restrict__ out, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
-    float* __restrict__ ws_snew, TextAppendDev ta)
+    float* __restrict__ ws_snew, TextAppendDev ta, TextDev text, int TS, int SP, int n_vis)
 {
     typedef DecTile<R> Tile;
     constexpr int NF = Tile::NF, NFA = Tile::NFA;
@@ -589,14 +707,46 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bool app = STEP && k_new != nullptr;
     const int G = Hq / Hkv;
     const int ngrp = (G + 15) >> 4;
-    const int split = blockIdx.x, b = blockIdx.z;
-    const int hk = blockIdx.y / ngrp, grp = blockIdx.y - hk * ngrp;
+    int split, by, b, tgin = -1, tslice = 0;
+    if constexpr (TEXT) {
+        const int gy = Hkv * ngrp;             // (KV head, head group) pairs per batch item
+        int id = blockIdx.x;
+        if (id >= n_vis) {
+            // text work-groups come in blocks of 8 (unit, slice) groups x Gm heads, numbered
+            // 8 * head + (group % 8) inside a block
+            const int Gm = min(G, 16), ngroup = (n_vis / S) * TS;
+            const int t = id - ((n_vis + 7) & ~7);
+            if (t < 0) return;                 // padding between the two index ranges
+            const int blk = t / (8 * Gm), w = t - blk * 8 * Gm;
+            const int grp_id = 8 * blk + (w & 7);
+            tgin = w >> 3;
+            if (grp_id >= ngroup) return;      // padding of the group count
+            tslice = grp_id % TS;
+            id = (grp_id / TS) * S;            // the unit's first visual index: same (b, h_kv, head group)
+        }
+        split = id % S;
+        const int yz = id / S;
+        by = yz % gy;
+        b = yz / gy;
+    } else {
+        split = blockIdx.x;
+        by = blockIdx.y;
+        b = blockIdx.z;
+    }
+    const int hk = by / ngrp, grp = by - hk * ngrp;
     const int h0 = hk * G + grp * 16;          // first query head of this group
     const int Gc = min(16, G - grp * 16);
     const int u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
-    if (STEP && ta.k && split == 0 && blockIdx.y == 0 && wave == 3) text_append_rows<bf16_t>(ta, b, Hkv, lane);
+    if (TEXT && tgin >= 0) {                   // a text work-group: one query head, one slice of the rows
+        if (tgin < Gc) {
+            const size_t row = (size_t)b * Hq + h0 + tgin;
+            text_partial(q, text, b, hk, row, tslice, TS, scale_log2, ws_m, ws_l, ws_acc, row * SP + S + tslice, big);
+        }
+        return;
+    }
+    if (STEP && ta.k && split == 0 && by == 0 && wave == 3) text_append_rows<bf16_t>(ta, b, Hkv, lane);
 
     // ---- everything that does not need seq_len goes out first -----------------------------
     // The sequence length costs a cold round trip to memory; the prologue operands (q, this
@@ -836,7 +986,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
                     const size_t row = (size_t)b * Hq + h0 + hh;
                     const int c = 16 * cb + n;
                     if (direct) out[row * D + c] = f32_to_bf16(acc[ii] / lh[ii]);
-                    else ws_acc[(row * S + split) * D + c] = acc[ii];
+                    else ws_acc[(row * SP + split) * D + c] = acc[ii];
                 }
             }
         }
@@ -845,7 +995,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
             for (int ii = 0; ii < 4; ++ii) {
                 const int hh = 4 * g + ii;
                 if (hh < Gc) {
-                    const size_t pidx = ((size_t)b * Hq + h0 + hh) * S + split;
+                    const size_t pidx = ((size_t)b * Hq + h0 + hh) * SP + split;
                     ws_m[pidx] = Mh[ii] + sbias[hh];
                     ws_l[pidx] = lh[ii];
                 }
@@ -861,7 +1011,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         if (out != nullptr) {
             out[row * D + c] = f32_to_bf16(0.f);
         } else {
-            const size_t pidx = row * S + split;
+            const size_t pidx = row * SP + split;
             ws_acc[pidx * D + c] = 0.f;
             if (c == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
         }
@@ -872,17 +1022,24 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 bool decode_mfma_supported(int dtype, int r) { return dtype == 1 && r >= 1 && r <= 128; }
 
 template <int R>
-static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf16_t* Kp, bf16_t* Vc, const float* Rr,
-                                 const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
-                                 float sl2, float* m, float* l, float* acc, int S, bf16_t* out, const bf16_t* k_new,
-                                 const bf16_t* v_new, float* snew, const TextAppendDev& ta)
+static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf16_t* Kp, bf16_t* Vc,
+                                 const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap,
+                                 int r, int tiles_all, float sl2, float* m, float* l, float* acc, int S, bf16_t* out,
+                                 const bf16_t* k_new, const bf16_t* v_new, float* snew, const TextAppendDev& ta,
+                                 const TextDev& text, int TS, int SP, int n_vis)
 {
-    if (k_new || ta.k)
-        hipLaunchKernelGGL((decode_split_mfma<R, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
-                           cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+    if (TS > 0)
+        hipLaunchKernelGGL((decode_split_mfma<R, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis);
+    else if (k_new || ta.k)
+        hipLaunchKernelGGL((decode_split_mfma<R, true, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis);
     else
-        hipLaunchKernelGGL((decode_split_mfma<R, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu, seq_len, Hq, Hkv,
-                           cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta);
+        hipLaunchKernelGGL((decode_split_mfma<R, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis);
 }
 
 // The fused append needs a free MFMA column next to the query heads: one group of fewer than 16.
@@ -891,16 +1048,27 @@ bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r)
     return mfma && decode_mfma_supported(dtype, r) && (Hq / Hkv) < 16;
 }
 
+// Text slices computed by work-groups of the split launch (dual path without a fused text append,
+// matrix-core kernels): how many slices for a segment of max_len rows (0 = not this way).
+int decode_text_slices(int dtype, bool mfma, int r, const TextDev* text, const TextAppendDev* tapp)
+{
+    if (!text || tapp || !mfma || !decode_mfma_supported(dtype, r)) return 0;
+    int ts = (text->max_len + 511) / 512;              // about 512 rows per slice
+    return ts < 1 ? 1 : (ts > DECODE_TEXT_SLICES_MAX ? DECODE_TEXT_SLICES_MAX : ts);
+}
+
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
                          float scale, void* out, float* ws, hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
+    const int TS = decode_text_slices(dtype, mfma, r, text, tapp);
+    const int SP = S + TS;                              // partials per (b, h_q)
     float* ws_m = ws;
-    float* ws_l = ws_m + rows * S;
-    float* ws_acc = ws_l + rows * S;
-    float* ws_snew = ws_acc + rows * S * D;            // [rows], fused append only
+    float* ws_l = ws_m + rows * SP;
+    float* ws_acc = ws_l + rows * SP;
+    float* ws_snew = ws_acc + rows * SP * D;           // [rows], fused append only
     const float sl2 = scale * 1.4426950408889634f;    // scores in the log2 domain
     const bool direct = S == 1 && text == nullptr && app == nullptr;   // a lone split of a plain call writes `out` itself
     hipError_t e;
@@ -908,17 +1076,22 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
     if (tapp && !text) return hipErrorInvalidValue;
     const TextAppendDev ta = tapp ? *tapp : TextAppendDev{};
     if (mfma && decode_mfma_supported(dtype, r)) {
-        const int G = Hq / Hkv;
-        dim3 grid(S, Hkv * ((G + 15) / 16), B);
+        const int G = Hq / Hkv, ngrp = (G + 15) / 16;
+        const int nunit = B * Hkv * ngrp, n_vis = nunit * S;
+        dim3 grid(S, Hkv * ngrp, B);                    // visual splits only: (split, (h_kv, head group), b)
+        if (TS > 0)                                     // one dimension: the splits, then the text work-groups
+            grid = dim3((unsigned)(((n_vis + 7) & ~7) + (G < 16 ? G : 16) * ((nunit * TS + 7) & ~7)));
         const bf16_t* q_ = (const bf16_t*)q;
         // the caches are written only by a fused append, whose caller handed them over writable
         bf16_t *k_ = const_cast<bf16_t*>((const bf16_t*)Kp), *v_ = const_cast<bf16_t*>((const bf16_t*)Vc);
         const bf16_t* kn = app ? (const bf16_t*)app->k_new : nullptr;
         const bf16_t* vn = app ? (const bf16_t*)app->v_new : nullptr;
+        const TextDev tx = TS > 0 ? *text : TextDev{};
 #define RK_CASE(RV)                                                                                        \
     case RV:                                                                                               \
-        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2, ws_m, ws_l, \
-                                 ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta);         \
+        launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2, ws_m,   \
+                                 ws_l, ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta, tx, TS, SP, \
+                                 n_vis);                                                                   \
         break;
         switch (keep_padded(r)) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
@@ -940,7 +1113,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (text) {
+    if (text && TS == 0) {
         const int U = B * Hkv, upad = (U + 7) & ~7, n_pad = upad - U;
         const unsigned tblocks = (unsigned)(upad * (Hq / Hkv));
         const bool wide = text->max_len > 128;       // bf16 only: the fp32 form would not fit its registers
@@ -954,11 +1127,15 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
             hipLaunchKernelGGL((decode_text_merge<bf16_t, 128>), dim3(tblocks), dim3(128), 0, st,
                                (const bf16_t*)q, *text, Hq, Hkv, sl2, ws_m, ws_l, ws_acc, S, (bf16_t*)out, n_pad);
     } else if (dtype == 0) {
-        hipLaunchKernelGGL(decode_merge<float>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
+        hipLaunchKernelGGL((decode_merge<float, 16>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
                            (float*)out, (const float*)nullptr, (const float*)nullptr, Hq, Hkv, cap,
                            (int32_t*)nullptr);
+    } else if (TS > 0) {
+        hipLaunchKernelGGL((decode_merge<bf16_t, 24>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
+                           (bf16_t*)out, (const float*)nullptr, (const bf16_t*)nullptr, Hq, Hkv, cap,
+                           (int32_t*)nullptr);
     } else {
-        hipLaunchKernelGGL(decode_merge<bf16_t>, dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, S,
+        hipLaunchKernelGGL((decode_merge<bf16_t, 16>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
                            (bf16_t*)out, app ? (const float*)ws_snew : (const float*)nullptr,
                            app ? (const bf16_t*)app->v_new : (const bf16_t*)nullptr, Hq, Hkv, cap,
                            app ? app->seq_len : (int32_t*)nullptr);

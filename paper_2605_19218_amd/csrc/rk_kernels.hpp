@@ -67,6 +67,10 @@ struct TextAppendDev {
     int32_t* len;            // device [B], bumped by the one wave that copies the rows
     int capacity;
 };
+// Dual path on the matrix-core kernels without a fused text append: the text attention runs as up to this
+// many slices in work-groups of the split launch, each writing a partial of its own (the workspace holds
+// S + DECODE_TEXT_SLICES_MAX partials per row); otherwise the text rows are handled by the merge kernel.
+constexpr int DECODE_TEXT_SLICES_MAX = 8;
 // whether launch_decode can take `app` for this shape (MFMA kernel with a free column: G < 16)
 bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r);
 // text == nullptr: visual segment only; otherwise the text segment joins the softmax in the merge kernel
@@ -75,7 +79,7 @@ bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r);
 // tapp != nullptr (needs text): row text.len[b] of the text segment receives k_new / v_new and the length is
 //                 bumped before the merge kernel reads it; text->max_len must already count the new row
 // tiles_all: 128-token tiles of the longest sequence; split s takes a balanced share of them
-// ws: partials, (S (d + 2) + 1) floats per (b, h_q)
+// ws: partials, ((S + DECODE_TEXT_SLICES_MAX) (d + 2) + 1) floats per (b, h_q)
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,

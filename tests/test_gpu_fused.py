@@ -197,8 +197,9 @@ def test_append_text_decode_fused(ctx, case):
             ref.max_len += 1
             assert seg.len.cpu().tolist() == lens_t
             check_out(got, oracle_dual(p, new["q"], lengths, seg, lens_t), dtype)
-            # the same arithmetic as the two separate calls: bit-identical
-            assert np.array_equal(got, decode_dual(ctx, p, q, ref.arg()))
+            # the two separate calls: same rows in the segment, same result up to the fp32 summation order
+            # (the plain dual call may run its text attention in slices next to the visual splits)
+            check_out(got, decode_dual(ctx, p, q, ref.arg()), dtype)
             assert torch.equal(seg.k, ref.k) and torch.equal(seg.v, ref.v)
     finally:
         rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
