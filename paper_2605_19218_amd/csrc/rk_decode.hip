@@ -132,10 +132,15 @@ template <typename T, int MC>
 __global__ __launch_bounds__(128) void decode_merge(const float* __restrict__ ws_m, const float* __restrict__ ws_l,
                                                     const float* __restrict__ ws_acc, int S, T* __restrict__ out,
                                                     const float* __restrict__ ws_snew, const T* __restrict__ v_new,
-                                                    int Hq, int Hkv, int cap, int32_t* __restrict__ seq_len)
+                                                    int Hq, int Hkv, int cap, int32_t* __restrict__ seq_len,
+                                                    int32_t* __restrict__ text_len, int text_cap)
 {
     const size_t row = blockIdx.x;         // b * Hq + hq
     const int tid = threadIdx.x;
+    if (text_len && tid == 0 && row % Hq == 0) {       // fused text append: the split launch stored the row
+        const int len = text_len[row / Hq];
+        if (len >= 0 && len < text_cap) text_len[row / Hq] = len + 1;
+    }
     const float* m = ws_m + row * S;
     const float* l = ws_l + row * S;
     const float* a = ws_acc + row * S * D + tid;
@@ -424,7 +429,12 @@ __global__ __launch_bounds__(128) void append_text_rows(const T* __restrict__ k_
 // split launch for one query head and rows [r0, r1) of the text segment; the result goes to a
 // workspace slot of its own as (m, l, acc) in the log2 domain, with no bias (Alg. 2 step 4), and
 // the plain merge kernel folds it with the visual partials.  `lds` needs 16 * 128 + 32 floats.
-__device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const TextDev& text, int b, int hk,
+// Fused text append (ta.k != NULL): row len[b] of the segment is the new token.  Every work-group
+// takes it from k_new / v_new, not from the segment, so nobody reads what this launch writes; the
+// work-group of the group's first head whose slice holds that row (`writer`) stores it, and the
+// merge kernel bumps len[b] once the whole launch is done.
+__device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const TextDev& text,
+                                             const TextAppendDev& ta, bool writer, int b, int hk, int Hkv,
                                              size_t row, int ts, int TS, float scale_log2,
                                              float* __restrict__ ws_m, float* __restrict__ ws_l,
                                              float* __restrict__ ws_acc, size_t pidx, float* lds)
@@ -435,12 +445,18 @@ __device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const
     float (*part)[D] = (float (*)[D])lds;
     float* sm_m = lds + TG * D;
     float* sm_l = sm_m + TG;
-    const int Mt = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
+    // rows stored in the segment, and rows attended: one more when a token is appended and fits
+    // (with an append text.max_len already counts the new row: the caller's bound plus one)
+    const int Ms = text.len ? min(max(text.len[b], 0), text.max_len) : text.max_len;
+    const bool add = ta.k != nullptr && text.len[b] >= 0 && text.len[b] < min(ta.capacity, text.max_len);
+    const int Mt = Ms + (add ? 1 : 0);
     // slices of whole passes, the last one takes what is left
     const int per = ((Mt + TS - 1) / TS + CHUNK - 1) / CHUNK * CHUNK;
     const int r0 = ts * per, r1 = min(r0 + per, Mt);
     const bf16_t* Kt = (const bf16_t*)text.k + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
     const bf16_t* Vt = (const bf16_t*)text.v + (int64_t)b * text.sb + (int64_t)hk * text.sh + cg * EPV;
+    const bf16_t* kn = add ? (const bf16_t*)ta.k_new + ((size_t)b * Hkv + hk) * D + cg * EPV : nullptr;
+    const bf16_t* vn = add ? (const bf16_t*)ta.v_new + ((size_t)b * Hkv + hk) * D + cg * EPV : nullptr;
 
     float qf[EPV];
     {
@@ -456,9 +472,11 @@ __device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const
     auto load_pass = [&](int base, uint4 (&kr)[NV], uint4 (&vr)[NV]) {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {           // rows past the end are clamped; their weight is 0
-            const int64_t off = (int64_t)min(base + tg + TG * k, Mt - 1) * text.st;
-            kr[k] = *(const uint4*)(Kt + off);
-            vr[k] = *(const uint4*)(Vt + off);
+            const int ri = base + tg + TG * k;
+            const int64_t off = (int64_t)max(min(ri, Ms - 1), 0) * text.st;
+            const bool fresh = add && ri == Ms;    // the appended row comes from the inputs
+            kr[k] = *(const uint4*)(fresh ? kn : Kt + off);
+            vr[k] = *(const uint4*)(fresh ? vn : Vt + off);
         }
     };
     if (r0 < r1) load_pass(r0, kraw, vraw);
@@ -524,6 +542,12 @@ __device__ __forceinline__ void text_partial(const bf16_t* __restrict__ q, const
         }
         ws_acc[pidx * D + tid] = num;
         if (tid == 0) { ws_m[pidx] = Mx; ws_l[pidx] = den; }
+    }
+    if (writer && add && Ms >= r0 && Ms < r0 + per && tg == 0) {   // one 16-lane group stores the new row
+        bf16_t* kd = (bf16_t*)ta.k + (int64_t)b * ta.sb + (int64_t)hk * ta.sh + (int64_t)Ms * ta.st + cg * EPV;
+        bf16_t* vd = (bf16_t*)ta.v + (int64_t)b * ta.sb + (int64_t)hk * ta.sh + (int64_t)Ms * ta.st + cg * EPV;
+        *(uint4*)kd = *(const uint4*)kn;
+        *(uint4*)vd = *(const uint4*)vn;
     }
 }
 
@@ -742,11 +766,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     if (TEXT && tgin >= 0) {                   // a text work-group: one query head, one slice of the rows
         if (tgin < Gc) {
             const size_t row = (size_t)b * Hq + h0 + tgin;
-            text_partial(q, text, b, hk, row, tslice, TS, scale_log2, ws_m, ws_l, ws_acc, row * SP + S + tslice, big);
+            text_partial(q, text, ta, tgin == 0 && grp == 0, b, hk, Hkv, row, tslice, TS, scale_log2, ws_m, ws_l,
+                         ws_acc, row * SP + S + tslice, big);
         }
         return;
     }
-    if (STEP && ta.k && split == 0 && by == 0 && wave == 3) text_append_rows<bf16_t>(ta, b, Hkv, lane);
 
     // ---- everything that does not need seq_len goes out first -----------------------------
     // The sequence length costs a cold round trip to memory; the prologue operands (q, this
@@ -1048,11 +1072,11 @@ bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r)
     return mfma && decode_mfma_supported(dtype, r) && (Hq / Hkv) < 16;
 }
 
-// Text slices computed by work-groups of the split launch (dual path without a fused text append,
-// matrix-core kernels): how many slices for a segment of max_len rows (0 = not this way).
-int decode_text_slices(int dtype, bool mfma, int r, const TextDev* text, const TextAppendDev* tapp)
+// Text slices computed by work-groups of the split launch (dual path on the matrix-core kernels):
+// how many slices for a segment of max_len rows (0 = not this way).
+int decode_text_slices(int dtype, bool mfma, int r, const TextDev* text)
 {
-    if (!text || tapp || !mfma || !decode_mfma_supported(dtype, r)) return 0;
+    if (!text || !mfma || !decode_mfma_supported(dtype, r)) return 0;
     int ts = (text->max_len + 511) / 512;              // about 512 rows per slice
     return ts < 1 ? 1 : (ts > DECODE_TEXT_SLICES_MAX ? DECODE_TEXT_SLICES_MAX : ts);
 }
@@ -1063,7 +1087,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
                          float scale, void* out, float* ws, hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
-    const int TS = decode_text_slices(dtype, mfma, r, text, tapp);
+    const int TS = decode_text_slices(dtype, mfma, r, text);
     const int SP = S + TS;                              // partials per (b, h_q)
     float* ws_m = ws;
     float* ws_l = ws_m + rows * SP;
@@ -1129,16 +1153,18 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
     } else if (dtype == 0) {
         hipLaunchKernelGGL((decode_merge<float, 16>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
                            (float*)out, (const float*)nullptr, (const float*)nullptr, Hq, Hkv, cap,
-                           (int32_t*)nullptr);
+                           (int32_t*)nullptr, (int32_t*)nullptr, 0);
     } else if (TS > 0) {
+        // with a fused text append the split launch has stored the new rows: the lengths move here
         hipLaunchKernelGGL((decode_merge<bf16_t, 24>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
                            (bf16_t*)out, (const float*)nullptr, (const bf16_t*)nullptr, Hq, Hkv, cap,
-                           (int32_t*)nullptr);
+                           (int32_t*)nullptr, tapp ? tapp->len : (int32_t*)nullptr,
+                           tapp ? (tapp->capacity < text->max_len ? tapp->capacity : text->max_len) : 0);
     } else {
         hipLaunchKernelGGL((decode_merge<bf16_t, 16>), dim3((unsigned)rows), dim3(128), 0, st, ws_m, ws_l, ws_acc, SP,
                            (bf16_t*)out, app ? (const float*)ws_snew : (const float*)nullptr,
                            app ? (const bf16_t*)app->v_new : (const bf16_t*)nullptr, Hq, Hkv, cap,
-                           app ? app->seq_len : (int32_t*)nullptr);
+                           app ? app->seq_len : (int32_t*)nullptr, (int32_t*)nullptr, 0);
     }
     return hipGetLastError();
 }

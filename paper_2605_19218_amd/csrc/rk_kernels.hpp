@@ -67,7 +67,7 @@ struct TextAppendDev {
     int32_t* len;            // device [B], bumped by the one wave that copies the rows
     int capacity;
 };
-// Dual path on the matrix-core kernels without a fused text append: the text attention runs as up to this
+// Dual path on the matrix-core kernels: the text attention runs as up to this
 // many slices in work-groups of the split launch, each writing a partial of its own (the workspace holds
 // S + DECODE_TEXT_SLICES_MAX partials per row); otherwise the text rows are handled by the merge kernel.
 constexpr int DECODE_TEXT_SLICES_MAX = 8;
