@@ -405,8 +405,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
-        from gpu_util import to_host
+        from paper_2605_19218_amd.torch_harness import to_host
         st, ly, hl = state[0], layers[0], host_layers[0]
         nb = B                                                  # the whole batch: one full decode step
         k_rows = torch.empty(B, Hkv, cap, r_main, device=dev, dtype=torch.bfloat16)

@@ -239,7 +239,8 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
 /* ---- Alg. 2 steps 1-3, 6 over the packed cache (App. C phases 1 and 2) ------
  * q~ = q R_r, b = q . delta_mu (delta_mu NULL = no bias), scores
  * (q~ . K~_n + b) * scale with scale = 1/sqrt(d) when `scale` <= 0, softmax over
- * the seq_len[b] cached tokens, out = P V.  q, out: [B,H_q,d] in L->dtype.
+ * the seq_len[b] cached tokens, out = P V.  q, out: [B,H_q,d] in L->dtype; q and
+ * both caches 16-byte aligned (the kernels read them in 16-byte pieces).
  * A sequence with seq_len[b] = 0 yields zeros.  Two launches (split-K, merge) as
  * in App. C, one when the plan has a single split.
  * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (max_seq_len > capacity),
@@ -260,7 +261,7 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
  * otherwise the call issues rk_append's and rk_decode_attn's launches.
  * L->max_seq_len bounds seq_len[b] BEFORE the call; L->seq_len is ignored in
  * favour of `seq_len` (device [B], read and written).  k_new, v_new: [B,H_kv,d],
- * q, out: [B,H_q,d], all L->dtype; k_new 16-byte aligned.  Workspace:
+ * q, out: [B,H_q,d], all L->dtype; q and k_new 16-byte aligned.  Workspace:
  * rk_decode_workspace_size of the layout with max_seq_len + 1.  A sequence
  * already at capacity is left untouched and attends over what it has.
  * Errors: INVALID_ARG, CAPACITY (max_seq_len + 1 > capacity; nothing is

@@ -280,7 +280,7 @@ rk_status rk_unpack_cache(rk_ctx* ctx, const rk_layout* L, const void* k_packed,
     if (s != RK_OK) return s;
     if ((k_rows && !k_packed) || (v_rows && !v_cache) || (!k_rows && !v_rows))
         return fail(ctx, RK_ERR_INVALID_ARG, "unpack: nothing to do or source missing");
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
@@ -305,7 +305,7 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     const FitWs w = fit_ws(L, keys->n_tokens);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))
         return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
@@ -341,7 +341,7 @@ rk_status rk_query_sigma(rk_ctx* ctx, const rk_layout* L, const void* q_window, 
     if (window < 1) return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: window must be >= 1");
     if (stride_b < 0 || stride_h < 0 || stride_w < D)
         return fail(ctx, RK_ERR_INVALID_ARG, "query_sigma: strides must be non-negative, stride_w >= %d", D);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
@@ -371,7 +371,7 @@ rk_status rk_fit_subspace(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
     const FitWs w = fit_ws(L, keys->n_tokens);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))
         return fail(ctx, RK_ERR_WORKSPACE, "fit workspace: need %zu bytes, 256-byte aligned", w.total);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
@@ -404,7 +404,7 @@ rk_status rk_gather_rotation(rk_ctx* ctx, const rk_layout* L, const float* R, co
     rk_status s = check_layout(ctx, L);
     if (s != RK_OK) return s;
     if (!R || !keep_idx || !R_r) return fail(ctx, RK_ERR_INVALID_ARG, "gather_rotation: NULL pointer");
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
@@ -434,7 +434,7 @@ rk_status rk_compress(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, cons
     }
     if (keys->n_tokens > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "compress: %d rows exceed capacity %d", keys->n_tokens, L->capacity);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
@@ -461,7 +461,7 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
     if (L->max_seq_len + 1 > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "append: %d + 1 rows exceed capacity %d", L->max_seq_len, L->capacity);
     if (L->batch > APP_TICKETS) return fail(ctx, RK_ERR_UNSUPPORTED, "append: batch too large");
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
@@ -482,8 +482,8 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     if (s != RK_OK) return s;
     if (!q || !k_packed || !v_cache || !R_r || !out || !L->seq_len)
         return fail(ctx, RK_ERR_INVALID_ARG, "decode: NULL pointer (q, k_packed, v_cache, R_r, out, seq_len)");
-    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15))
-        return fail(ctx, RK_ERR_INVALID_ARG, "decode: caches must be 16-byte aligned");
+    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)q & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "decode: q and the caches must be 16-byte aligned");
     if (L->max_seq_len > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "decode: max_seq_len %d exceeds capacity %d", L->max_seq_len, L->capacity);
     TextDev td{};
@@ -491,7 +491,6 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     if (text) {
         s = check_text(ctx, text, tk_new != nullptr);
         if (s != RK_OK) return s;
-        if ((uintptr_t)q & 15) return fail(ctx, RK_ERR_INVALID_ARG, "decode (dual): q must be 16-byte aligned");
         td = TextDev{text->k, text->v, text->stride_b, text->stride_h, text->stride_t, text->len, text->max_len};
         if (tk_new) {
             if (!tv_new || ((uintptr_t)tk_new & 15) || ((uintptr_t)tv_new & 15))
@@ -507,7 +506,7 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     const size_t need = rk_decode_workspace_size(ctx, L);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
         return fail(ctx, RK_ERR_WORKSPACE, "decode workspace: need %zu bytes, 16-byte aligned", need);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
@@ -562,8 +561,8 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
     if (s != RK_OK) return s;
     if (!k_new || !v_new || !q || !R_r || !k_packed || !v_cache || !seq_len || !out)
         return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: NULL pointer");
-    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)k_new & 15))
-        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: caches and k_new must be 16-byte aligned");
+    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)k_new & 15) || ((uintptr_t)q & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: q, k_new and the caches must be 16-byte aligned");
     if (L->max_seq_len + 1 > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "append_decode: %d + 1 rows exceed capacity %d", L->max_seq_len,
                     L->capacity);
@@ -575,7 +574,7 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
     const size_t need = rk_decode_workspace_size(ctx, &La);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
         return fail(ctx, RK_ERR_WORKSPACE, "append_decode workspace: need %zu bytes, 16-byte aligned", need);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
@@ -614,7 +613,7 @@ rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, c
     if (text->max_len + 1 > text->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "append_text: %d + 1 rows exceed capacity %d", text->max_len,
                     text->capacity);
-    if (ctx->device == RK_DEVICE_NONE) return RK_ERR_NO_DEVICE;
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
     DeviceGuard dev(ctx->device);
     hipError_t e = dev.status;
     if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
