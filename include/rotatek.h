@@ -249,6 +249,25 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
                          const void* v_cache, const float* R_r, const float* delta_mu, float scale,
                          void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- rk_decode_attn for callers that cannot allocate ---------------------------
+ * For code that may not call hipMalloc or hand over a buffer of its own making:
+ * work under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same arguments, kernels and results as rk_decode_attn, without the
+ * workspace: the split-K partials go to a scratch array built into the library
+ * (RK_STATIC_SCRATCH_BYTES of device memory that every GPU the library runs on
+ * holds until the process ends).  The call allocates and frees nothing.
+ * A shape whose rk_decode_workspace_size() exceeds RK_STATIC_SCRATCH_BYTES is
+ * refused with RK_ERR_WORKSPACE (text in rk_last_error) and nothing is launched.
+ * All calls on one GPU share that GPU's array, from every context and stream:
+ * calls that overlap in time on one GPU race on it and must be ordered by the
+ * caller (calls on one stream are).  The array keeps the last call's partials;
+ * nothing in it needs clearing between calls.
+ * Errors: as rk_decode_attn.                                                    */
+#define RK_STATIC_SCRATCH_BYTES (8u << 20)
+rk_status rk_decode_attn_static(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                                const void* v_cache, const float* R_r, const float* delta_mu, float scale,
+                                void* out, void* stream);
+
 /* ---- rk_append followed by rk_decode_attn, fused ------------------------------
  * One decode step of a layer whose new token joins the rotated cache (Sec. 3.2
  * Step (1) then Alg. 2): row seq_len[b] of k_packed / v_cache receives

@@ -28,8 +28,9 @@ EXPORTS = [
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
     "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace", "rk_query_sigma", "rk_append_decode_attn",
-    "rk_append_text_decode_attn_dual",
+    "rk_append_text_decode_attn_dual", "rk_decode_attn_static",
 ]
+RK_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class rk_layout(C.Structure):
@@ -99,6 +100,7 @@ def lib():
         L.rk_compress.argtypes = [vp, PL, PR, vp, vp, PR, vp, vp, vp]
         L.rk_append.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp]
         L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+        L.rk_decode_attn_static.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp]
         L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
         L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
         L.rk_append_text_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
@@ -293,6 +295,13 @@ def rk_decode_attn(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, sca
     _check(ctx, lib().rk_decode_attn(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache), _ptr(R_r),
                                      _ptr(delta_mu), float(scale), _ptr(out), _ptr(workspace), wb,
                                      _stream(stream)))
+
+
+def rk_decode_attn_static(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, scale: float, out,
+                          stream=None) -> None:
+    """rk_decode_attn without a workspace: the partials live in the library's built-in scratch array."""
+    _check(ctx, lib().rk_decode_attn_static(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache),
+                                            _ptr(R_r), _ptr(delta_mu), float(scale), _ptr(out), _stream(stream)))
 
 
 def rk_decode_attn_dual(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, text: Text, scale: float, out,

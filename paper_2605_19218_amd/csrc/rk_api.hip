@@ -14,8 +14,17 @@ struct rk_ctx {
     int force_generic;
     int decode_splits;
     int32_t* tickets;     // device: APP_TICKETS zero-initialised counters (one per batch item, rk_append)
+    void* static_scratch; // this device's copy of `scratch` below (its device address), for rk_decode_attn_static
     char err[256];
 };
+
+// Split-K partials of rk_decode_attn_static, for callers that cannot hand over a workspace they
+// allocated.  Every GPU the library runs on holds its own copy until the process ends.  In host code
+// this name is only a stand-in for the symbol: the device address of a GPU's copy comes from
+// hipGetSymbolAddress (rk_create, with that device current) and is what kernels and copies receive.
+// Nothing in it has to start at zero: the merge kernel reads exactly the partial slots that the split
+// kernel of the same call has written.
+static __device__ __align__(256) unsigned char scratch[RK_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -198,6 +207,12 @@ rk_status rk_create(rk_ctx** out, int device)
             return RK_ERR_HIP;
         }
         if (hipMemset(c->tickets, 0, tb) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipFree(c->tickets);
+            delete c;
+            return RK_ERR_HIP;
+        }
+        // this device's copy of the static scratch array (each GPU has its own, at its own address)
+        if (hipGetSymbolAddress(&c->static_scratch, HIP_SYMBOL(scratch)) != hipSuccess || !c->static_scratch) {
             (void)hipFree(c->tickets);
             delete c;
             return RK_ERR_HIP;
@@ -475,7 +490,7 @@ rk_status rk_append(rk_ctx* ctx, const rk_layout* L, const void* k_new, const vo
 static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
                                const void* v_cache, const float* R_r, const float* delta_mu, const rk_text* text,
                                const void* tk_new, const void* tv_new, float scale, void* out, void* workspace,
-                               size_t workspace_bytes, void* stream)
+                               size_t workspace_bytes, void* stream, bool use_static = false)
 {
     if (!ctx) return RK_ERR_INVALID_ARG;
     rk_status s = check_layout(ctx, L);
@@ -504,7 +519,14 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
         }
     }
     const size_t need = rk_decode_workspace_size(ctx, L);
-    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
+    if (use_static) {
+        if (need > (size_t)RK_STATIC_SCRATCH_BYTES)
+            return fail(ctx, RK_ERR_WORKSPACE, "decode (static scratch): this shape needs %zu bytes of partials, the "
+                        "built-in scratch holds %zu; use rk_decode_attn with a workspace", need,
+                        (size_t)RK_STATIC_SCRATCH_BYTES);
+        if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
+        workspace = ctx->static_scratch;            // the device address taken at rk_create, never the symbol
+    } else if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))
         return fail(ctx, RK_ERR_WORKSPACE, "decode workspace: need %zu bytes, 16-byte aligned", need);
     if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
 
@@ -527,6 +549,14 @@ rk_status rk_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* q, const v
 {
     return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, nullptr, nullptr, nullptr, scale, out,
                          workspace, workspace_bytes, stream);
+}
+
+rk_status rk_decode_attn_static(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,
+                                const void* v_cache, const float* R_r, const float* delta_mu, float scale,
+                                void* out, void* stream)
+{
+    return decode_common(ctx, L, q, k_packed, v_cache, R_r, delta_mu, nullptr, nullptr, nullptr, scale, out,
+                         nullptr, 0, stream, true);
 }
 
 rk_status rk_decode_attn_dual(rk_ctx* ctx, const rk_layout* L, const void* q, const void* k_packed,

@@ -262,3 +262,20 @@ def test_c99_caller_builds_and_runs(tmp_path):
         assert int(ws) == rk.rk_decode_workspace_size(c, layout())
     finally:
         rk.rk_destroy(c)
+
+
+def test_static_scratch_entry_validates_on_the_host(ctx):
+    """rk_decode_attn_static: the same argument checks as rk_decode_attn, the size limit of the built-in
+    scratch array, and only then the missing device."""
+    call = lambda lay, q=PTR: status_of(rk.rk_decode_attn_static, ctx, lay, q, PTR, PTR, PTR, None, 0.0, PTR)
+    assert call(layout()) == rk.RK_ERR_NO_DEVICE                     # valid, fits: only the device is missing
+    assert call(layout(), q=PTR + 2) == rk.RK_ERR_INVALID_ARG        # misaligned query
+    assert call(layout(max_seq_len=2048)) == rk.RK_ERR_CAPACITY
+    big = layout(batch=4096, n_q_heads=64, n_kv_heads=64, capacity=1 << 16, max_seq_len=1 << 16)
+    assert rk.rk_decode_workspace_size(ctx, big) > rk.RK_STATIC_SCRATCH_BYTES
+    assert call(big) == rk.RK_ERR_WORKSPACE
+    assert "scratch" in rk.lib().rk_last_error(ctx).decode()
+    # the header's constant and the binding's agree
+    text = open(os.path.join(ROOT, "include", "rotatek.h")).read()
+    m = re.search(r"#define RK_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == rk.RK_STATIC_SCRATCH_BYTES
