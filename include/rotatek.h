@@ -66,7 +66,10 @@ enum {
 /* rk_set_option keys */
 enum {
     RK_OPT_FORCE_GENERIC = 1, /* value != 0: use the plain (non-MFMA) kernels everywhere  */
-    RK_OPT_DECODE_SPLITS = 2  /* value > 0: fix the split-K factor N_s; 0 = automatic     */
+    RK_OPT_DECODE_SPLITS = 2, /* value > 0: fix the split-K factor N_s; 0 = automatic     */
+    RK_OPT_FUSE_MERGE = 3     /* value == 0: rk_decode_attn always merges its partials in a
+                                 second launch (default 1: inside the split launch where
+                                 the shape allows it)                                    */
 };
 
 #define RK_DEVICE_NONE (-1)

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "librotatek.so")
 RK_OK, RK_ERR_INVALID_ARG, RK_ERR_UNSUPPORTED, RK_ERR_CAPACITY, RK_ERR_WORKSPACE, RK_ERR_HIP, RK_ERR_NO_DEVICE = range(7)
 RK_F32, RK_BF16 = 0, 1
 RK_FIT_CENTER = 1
-RK_OPT_FORCE_GENERIC, RK_OPT_DECODE_SPLITS = 1, 2
+RK_OPT_FORCE_GENERIC, RK_OPT_DECODE_SPLITS, RK_OPT_FUSE_MERGE = 1, 2, 3
 RK_DEVICE_NONE = -1
 
 EXPORTS = [

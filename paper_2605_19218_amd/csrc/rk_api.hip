@@ -13,6 +13,8 @@ struct rk_ctx {
     int n_cu;
     int force_generic;
     int decode_splits;
+    int fuse_merge;       // fold the split-K merge into the split launch where the shape allows it
+    int xcd_deal_ok;      // work-groups with equal (linear index mod 8) share an XCD on this device (probed)
     int32_t* tickets;     // device: APP_TICKETS zero-initialised counters (one per batch item, rk_append)
     void* static_scratch; // this device's copy of `scratch` below (its device address), for rk_decode_attn_static
     char err[256];
@@ -47,6 +49,7 @@ rk_status hip_fail(rk_ctx* ctx, hipError_t e, const char* what)
 }
 
 constexpr int APP_TICKETS = 1 << 16;   // >= batch
+constexpr int DEC_COUNTERS = 1 << 16;  // units (b, h_kv, head group) whose split-K merge can ride in the split launch
 
 size_t elem_size(int dtype) { return dtype == RK_F32 ? 4 : 2; }
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -136,7 +139,10 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_o
     int S;
     if (ctx && ctx->decode_splits > 0) S = ctx->decode_splits;
     else {
-        long target = 2L * n_cu;          // two 4-wave work-groups per compute unit
+        // one 4-wave work-group per compute unit: a second one gets its memory requests served only
+        // after the first one's (measured: its prologue then ends 10 us later), and every work-group
+        // pays its own prologue and partial
+        long target = n_cu;
         S = (int)((target + units - 1) / units);
         if (S > 64) S = 64;
         // a split shorter than 512 tokens (four 32-token tiles per wave) no longer amortises its
@@ -194,13 +200,14 @@ rk_status rk_create(rk_ctx** out, int device)
     memset(c, 0, sizeof(*c));
     c->device = device;
     c->n_cu = 256;
+    c->fuse_merge = 1;
     if (device != RK_DEVICE_NONE) {
         if (device < 0) { delete c; return RK_ERR_INVALID_ARG; }
         hipDeviceProp_t prop;
         hipError_t e = hipGetDeviceProperties(&prop, device);
         if (e != hipSuccess) { delete c; return RK_ERR_HIP; }
         c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        const size_t tb = (size_t)APP_TICKETS * sizeof(int32_t);
+        const size_t tb = (size_t)(APP_TICKETS + DEC_COUNTERS) * sizeof(int32_t);
         DeviceGuard dev(device);
         if (dev.status != hipSuccess || hipMalloc((void**)&c->tickets, tb) != hipSuccess) {
             delete c;
@@ -211,6 +218,14 @@ rk_status rk_create(rk_ctx** out, int device)
             delete c;
             return RK_ERR_HIP;
         }
+        // the folded merge needs all work-groups of a unit behind one L2: check how this device deals them
+        bool same_xcd = false;
+        if (probe_xcd_deal(c->tickets, &same_xcd) != hipSuccess) {
+            (void)hipFree(c->tickets);
+            delete c;
+            return RK_ERR_HIP;
+        }
+        c->xcd_deal_ok = same_xcd ? 1 : 0;
         // this device's copy of the static scratch array (each GPU has its own, at its own address)
         if (hipGetSymbolAddress(&c->static_scratch, HIP_SYMBOL(scratch)) != hipSuccess || !c->static_scratch) {
             (void)hipFree(c->tickets);
@@ -240,6 +255,7 @@ rk_status rk_set_option(rk_ctx* ctx, int32_t key, int64_t value)
     if (!ctx) return RK_ERR_INVALID_ARG;
     switch (key) {
         case RK_OPT_FORCE_GENERIC: ctx->force_generic = value != 0; return RK_OK;
+        case RK_OPT_FUSE_MERGE: ctx->fuse_merge = value != 0; return RK_OK;
         case RK_OPT_DECODE_SPLITS:
             if (value < 0 || value > 4096) return fail(ctx, RK_ERR_INVALID_ARG, "decode splits %lld outside 0..4096", (long long)value);
             ctx->decode_splits = (int)value;
@@ -538,7 +554,9 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)L->head_dim);
     e = launch_decode(L->dtype, use_mfma_decode(ctx, L), L->batch, L->n_q_heads, L->n_kv_heads, L->capacity,
                       L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, nullptr,
-                      tk_new ? &ta : nullptr, sc, out, (float*)workspace, as_stream(stream));
+                      tk_new ? &ta : nullptr, sc, out, (float*)workspace,
+                      ctx->fuse_merge && ctx->xcd_deal_ok ? ctx->tickets + APP_TICKETS : nullptr, DEC_COUNTERS,
+                      as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }
@@ -625,7 +643,7 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
     }
     e = launch_decode(L->dtype, mfma, L->batch, L->n_q_heads, L->n_kv_heads, L->capacity, L->keep, S, tiles, q,
                       k_packed, v_cache, R_r, delta_mu, seq_len, nullptr, fused ? &app : nullptr, nullptr, sc, out,
-                      (float*)workspace, st);
+                      (float*)workspace, nullptr, 0, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }

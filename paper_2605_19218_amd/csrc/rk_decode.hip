@@ -608,6 +608,43 @@ __device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restric
     load_tile_v<R>(T, Vu, tok0, lane);
 }
 
+// Fold of S partials (m, l, acc) for one (row, 8 channels) in ascending order, MC at a time: every
+// load of a chunk is issued before the first use, so a chunk costs one round trip to the L2.
+template <int MC>
+__device__ __forceinline__ void fold_partials(const float* pm, const float* pl, const float* pa, int S, float& M,
+                                              float& den, f32x4& n0, f32x4& n1)
+{
+    for (int i0 = 0; i0 < S; i0 += MC) {
+        f32x4 a0[MC], a1[MC];
+        float mv[MC], lv[MC];
+#pragma unroll
+        for (int k = 0; k < MC; ++k) {
+            const int i = min(i0 + k, S - 1);
+            a0[k] = *(const f32x4*)(pa + (size_t)i * D);
+            a1[k] = *(const f32x4*)(pa + (size_t)i * D + 4);
+            mv[k] = i0 + k < S ? pm[i] : NEG_INF;
+            lv[k] = pl[i];
+        }
+        float Mc = M;
+#pragma unroll
+        for (int k = 0; k < MC; ++k) Mc = fmaxf(Mc, mv[k]);
+        if (Mc > NEG_INF) {
+            const float resc = exp2f(M - Mc);                   // 0 on the first non-empty chunk
+            den *= resc;
+            n0 *= resc;
+            n1 *= resc;
+#pragma unroll
+            for (int k = 0; k < MC; ++k) {
+                const float w = exp2f(mv[k] - Mc);              // 2^(-inf) = 0 for empty and absent partials
+                den = fmaf(lv[k], w, den);
+                n0 += a0[k] * w;
+                n1 += a1[k] * w;
+            }
+            M = Mc;
+        }
+    }
+}
+
 template <int R>
 struct DecState {
     float m_run, l_run;
@@ -703,13 +740,14 @@ __device__ __forceinline__ void compute_tile(DecTile<R>& T, DecState<R>& st, con
 // the heads of a group, which read the same text rows, then have indices that agree modulo 8, i.e.
 // run on one XCD (work-groups are dealt round-robin to the 8 XCDs) at about the same time, and share
 // its L2.
-template <int R, bool STEP, bool TEXT>
+template <int R, bool STEP, bool TEXT, bool FUSED>
 __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bf16_t* __restrict__ q, bf16_t* Kp, bf16_t* Vc, const float* __restrict__ Rr,
     const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
-    float scale_log2, float* __restrict__ ws_m, float* __restrict__ ws_l, float* __restrict__ ws_acc, int S,
+    float scale_log2, float* ws_m, float* ws_l, float* ws_acc, int S,
     bf16_t* __restrict__ out, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
-    float* __restrict__ ws_snew, TextAppendDev ta, TextDev text, int TS, int SP, int n_vis)
+    float* __restrict__ ws_snew, TextAppendDev ta, TextDev text, int TS, int SP, int n_vis,
+    bf16_t* __restrict__ out_merged, int32_t* done)
 {
     typedef DecTile<R> Tile;
     constexpr int NF = Tile::NF, NFA = Tile::NFA;
@@ -721,7 +759,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     __shared__ float sbias[16];
     __shared__ __attribute__((aligned(16))) float sdm[D];
     __shared__ float sm_m[4][16], sm_l[4][16];
-
+    __shared__ int sm_last;
     const bool direct = out != nullptr;     // the only split of a single-path call writes the result itself
     // Fused frozen-R append (k_new != NULL; the host guarantees G < 16 and never combines it
     // with `direct`): k_new rides through the q~ MFMAs as column 15, which the query heads
@@ -731,8 +769,22 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bool app = STEP && k_new != nullptr;
     const int G = Hq / Hkv;
     const int ngrp = (G + 15) >> 4;
-    int split, by, b, tgin = -1, tslice = 0;
-    if constexpr (TEXT) {
+    int split, by, b, tgin = -1, tslice = 0, unit = 0;
+    if constexpr (FUSED) {
+        // One-dimensional grid.  Work-groups are dealt to the XCDs round-robin by their linear index, so
+        // index & 7 is this work-group's XCD: all S work-groups of a unit get the same XCD (unit = 8 ul + xcd)
+        // and therefore share an L2, which is what lets the unit's last work-group read the others'
+        // partials without any device-wide cache write-back (n_vis = number of units here; the host
+        // checks the deal once per context, see rk_create).  Units go fastest inside an XCD's slots, so
+        // every unit has work-groups among the first dispatched and among the last.
+        const int id = blockIdx.x, slot = id >> 3, upx = (n_vis + 7) >> 3, ul = slot % upx;
+        split = slot / upx;
+        unit = 8 * ul + (id & 7);
+        if (unit >= n_vis) return;
+        const int gy = Hkv * ngrp;
+        by = unit % gy;
+        b = unit / gy;
+    } else if constexpr (TEXT) {
         const int gy = Hkv * ngrp;             // (KV head, head group) pairs per batch item
         int id = blockIdx.x;
         if (id >= n_vis) {
@@ -774,7 +826,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 
     // ---- everything that does not need seq_len goes out first -----------------------------
     // The sequence length costs a cold round trip to memory; the prologue operands (q, this
-    // thread's R_r pieces, delta_mu) and the first two tiles of every wave are requested before
+    // thread's R_r pieces, delta_mu) and the first tile of every wave are requested before
     // it is used.  The tile prefetch is speculative: it assumes the split is full and only
     // checks that the tile lies inside the cache slab; rows past the real end are masked or
     // skipped later (the prologue is on the kernel's critical path: while it runs only the
@@ -797,24 +849,28 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const float* Ru = Rr + (size_t)u * D * r;
     bf16x8 qfrag[4];
     float ra[NBW][4][8];
+    float dmv;                                     // delta_mu goes through LDS (one value per thread)
     {
+        // Every load below is unconditional (indices clamped, the value discarded afterwards): a load
+        // under a per-lane condition compiles to a branch, and past a branch the compiler no longer knows
+        // how many loads are outstanding, so the first use of R_r would wait for the tile prefetch too
+        // (a round trip to HBM under full load instead of an L2 hit).
         const bool newcol = app && n == 15;
-        const bf16_t* qrow = newcol ? k_new + (size_t)u * D + 8 * g : q + ((size_t)b * Hq + h0 + n) * D + 8 * g;
+        const bf16_t* qrow = newcol ? k_new + (size_t)u * D + 8 * g
+                                    : q + ((size_t)b * Hq + h0 + min(n, Gc - 1)) * D + 8 * g;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            qfrag[i] = (n < Gc || newcol) ? *(const bf16x8*)(qrow + 32 * i) : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        for (int i = 0; i < 4; ++i) qfrag[i] = *(const bf16x8*)(qrow + 32 * i);
 #pragma unroll
         for (int bw = 0; bw < NBW; ++bw) {
-            const int jb = wave + 4 * bw;
+            const int col = min(16 * (wave + 4 * bw) + n, r - 1);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj)
-                    ra[bw][i][jj] = 16 * jb + n < r ? Ru[(32 * i + 8 * g + jj) * r + 16 * jb + n] : 0.f;
+                for (int jj = 0; jj < 8; ++jj) ra[bw][i][jj] = Ru[(32 * i + 8 * g + jj) * r + col];
         }
+        const float* dp = dmu ? dmu + (size_t)u * D : Ru;     // any readable address when there is no bias
+        dmv = dp[tid & (D - 1)];
     }
-    float dmv = 0.f;                               // delta_mu goes through LDS (one value per thread)
-    if (dmu && tid < D) dmv = dmu[(size_t)u * D + tid];
 
     Tile TA, TB;
 #pragma unroll
@@ -832,11 +888,16 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         TA.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
         TB.vf[cb] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
     }
-    // this wave's tiles are wave, wave + 4, ...; tile k starts at tokA + 128 k
-    const int tokA = t0 + wave * 32;
+    // This wave's tiles are wave, wave + 4, ...; tile k starts at tokA + 128 k.  Only the first is
+    // requested here: the compute unit's queue of memory requests is full within a microsecond of
+    // the launch, so a second tile ahead of the prologue would only delay the wave on its way to
+    // the q~ arithmetic (the instructions issue in order); it follows right behind that arithmetic.
+    // Unconditional like the prologue loads: a tile outside the split is "loaded" with every lane on
+    // one 16-byte piece of the slab's first tile and never computed.
+    const int tokA = t0 + wave * 32, tokB = tokA + 128;
     const int t_spec = min(t1_full, cap);          // the slab ends at cap (a multiple of 32)
-    if (tokA + 32 <= t_spec) load_tile<R>(TA, Ku, Vu, tokA, lane);
-    if (tokA + 128 + 32 <= t_spec) load_tile<R>(TB, Ku, Vu, tokA + 128, lane);
+    const bool okA = tokA + 32 <= t_spec, okB = tokB + 32 <= t_spec;
+    load_tile<R>(TA, Ku, Vu, okA ? tokA : 0, okA ? lane : 0);
 
     const int L = min(max(seq_raw, 0), cap);
     const int t1 = min(t1_full, L);
@@ -853,7 +914,20 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         // wave and pass, R_r as bf16 head + remainder (two MFMAs per 32 channels).  Lane (g, n)
         // ends up with q~[head n][16 jb + 4 g + 0..3]: one 16-byte store to LDS, one barrier.
         {
-            if (tid < D) sdm[tid] = dmv;
+            // discard what the clamped prologue loads fetched for heads and columns that do not exist
+            if (!(n < Gc || (app && n == 15))) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) qfrag[i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int bw = 0; bw < NBW; ++bw)
+                if (16 * (wave + 4 * bw) + n >= r) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < 8; ++jj) ra[bw][i][jj] = 0.f;
+                }
+            if (tid < D) sdm[tid] = dmu ? dmv : 0.f;
 #pragma unroll
             for (int bw = 0; bw < NBW; ++bw) {
                 const int jb = wave + 4 * bw;
@@ -915,6 +989,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
                 Vc[(size_t)u * cap * D + vidx(seq_raw, c)] = v_new[(size_t)u * D + c];
             }
         }
+
+        load_tile<R>(TB, Ku, Vu, okB ? tokB : 0, okB ? lane : 0);
 
         // B operands of the score MFMAs: q~ of head n, split into bf16 head + remainder
         bf16x8 qh[NFA], ql[NFA];
@@ -1025,20 +1101,53 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
                 }
             }
         }
-        return;
+    } else {
+        // ---- empty split: zeros with m = -inf (or zeros to `out` if it is the only split) ----
+        for (int idx = tid; idx < Gc * D; idx += 256) {
+            int hh = idx >> 7, c = idx & 127;
+            const size_t row = (size_t)b * Hq + h0 + hh;
+            if (out != nullptr) {
+                out[row * D + c] = f32_to_bf16(0.f);
+            } else {
+                const size_t pidx = row * SP + split;
+                ws_acc[pidx * D + c] = 0.f;
+                if (c == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
+            }
+        }
     }
 
-    // ---- empty split: zeros with m = -inf (or zeros to `out` if it is the only split) ----
-    for (int idx = tid; idx < Gc * D; idx += 256) {
-        int hh = idx >> 7, c = idx & 127;
-        const size_t row = (size_t)b * Hq + h0 + hh;
-        if (out != nullptr) {
-            out[row * D + c] = f32_to_bf16(0.f);
-        } else {
-            const size_t pidx = row * SP + split;
-            ws_acc[pidx * D + c] = 0.f;
-            if (c == 0) { ws_m[pidx] = NEG_INF; ws_l[pidx] = 0.f; }
+    if constexpr (FUSED) {
+        // ---- App. C phase 2 inside the split launch: the unit's last work-group folds the partials ----
+        // Vector stores stay counted until the L2 has acknowledged them, so after this wait and the
+        // barrier every partial of this work-group is in the XCD's L2, and the counter increment that
+        // follows is ordered behind them.  The S work-groups of a unit run on one XCD (see the index
+        // mapping above), so the one that draws the last ticket finds all S partials in that same L2.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0)
+            sm_last = __hip_atomic_fetch_add(done + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == S - 1;
+        __syncthreads();
+        if (!sm_last) return;
+        const int hh = tid >> 4, c0 = (tid & 15) * 8;           // thread = (head, 8 channels)
+        if (hh < Gc) {
+            const size_t row = (size_t)b * Hq + h0 + hh;
+            const float* pm = ws_m + row * SP;
+            const float* pl = ws_l + row * SP;
+            const float* pa = ws_acc + row * SP * D + c0;
+            float M = NEG_INF, den = 0.f;
+            f32x4 n0 = (f32x4){0.f, 0.f, 0.f, 0.f}, n1 = n0;
+            if (S <= 8) fold_partials<8>(pm, pl, pa, S, M, den, n0, n1);     // one round trip to the L2
+            else fold_partials<16>(pm, pl, pa, S, M, den, n0, n1);
+            const float inv = (M > NEG_INF) ? 1.f / den : 0.f;
+            uint4 pk;
+            pk.x = (uint32_t)f32_to_bf16(n0[0] * inv) | ((uint32_t)f32_to_bf16(n0[1] * inv) << 16);
+            pk.y = (uint32_t)f32_to_bf16(n0[2] * inv) | ((uint32_t)f32_to_bf16(n0[3] * inv) << 16);
+            pk.z = (uint32_t)f32_to_bf16(n1[0] * inv) | ((uint32_t)f32_to_bf16(n1[1] * inv) << 16);
+            pk.w = (uint32_t)f32_to_bf16(n1[2] * inv) | ((uint32_t)f32_to_bf16(n1[3] * inv) << 16);
+            *(uint4*)(out_merged + row * D + c0) = pk;
         }
+        __syncthreads();
+        if (tid == 0) done[unit] = 0;                           // ready for the next launch on this context
     }
 }
 
@@ -1050,20 +1159,24 @@ static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf1
                                  const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap,
                                  int r, int tiles_all, float sl2, float* m, float* l, float* acc, int S, bf16_t* out,
                                  const bf16_t* k_new, const bf16_t* v_new, float* snew, const TextAppendDev& ta,
-                                 const TextDev& text, int TS, int SP, int n_vis)
+                                 const TextDev& text, int TS, int SP, int n_vis, bf16_t* out_merged, int32_t* done)
 {
-    if (TS > 0)
-        hipLaunchKernelGGL((decode_split_mfma<R, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+    if (out_merged)
+        hipLaunchKernelGGL((decode_split_mfma<R, false, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis);
+                           SP, n_vis, out_merged, done);
+    else if (TS > 0)
+        hipLaunchKernelGGL((decode_split_mfma<R, false, true, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis, out_merged, done);
     else if (k_new || ta.k)
-        hipLaunchKernelGGL((decode_split_mfma<R, true, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+        hipLaunchKernelGGL((decode_split_mfma<R, true, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis);
+                           SP, n_vis, out_merged, done);
     else
-        hipLaunchKernelGGL((decode_split_mfma<R, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+        hipLaunchKernelGGL((decode_split_mfma<R, false, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis);
+                           SP, n_vis, out_merged, done);
 }
 
 // The fused append needs a free MFMA column next to the query heads: one group of fewer than 16.
@@ -1084,7 +1197,7 @@ int decode_text_slices(int dtype, bool mfma, int r, const TextDev* text)
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
-                         float scale, void* out, float* ws, hipStream_t st)
+                         float scale, void* out, float* ws, int32_t* counters, int n_counters, hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
     const int TS = decode_text_slices(dtype, mfma, r, text);
@@ -1101,10 +1214,20 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
     const TextAppendDev ta = tapp ? *tapp : TextAppendDev{};
     if (mfma && decode_mfma_supported(dtype, r)) {
         const int G = Hq / Hkv, ngrp = (G + 15) / 16;
-        const int nunit = B * Hkv * ngrp, n_vis = nunit * S;
+        const int nunit = B * Hkv * ngrp;
+        int n_vis = nunit * S;
         dim3 grid(S, Hkv * ngrp, B);                    // visual splits only: (split, (h_kv, head group), b)
         if (TS > 0)                                     // one dimension: the splits, then the text work-groups
             grid = dim3((unsigned)(((n_vis + 7) & ~7) + (G < 16 ? G : 16) * ((nunit * TS + 7) & ~7)));
+        // Merge folded into the split launch: a plain decode with several splits whose units deal
+        // out evenly over the 8 XCDs (the splits of a unit share an XCD there; an uneven deal would
+        // leave XCDs idle, which costs more than the second launch saves)
+        const bool fused_merge = !text && !app && S >= 2 && counters && nunit <= n_counters &&
+                                 (nunit % 8 == 0 || nunit >= 160);
+        if (fused_merge) {
+            grid = dim3((unsigned)(8 * ((nunit + 7) / 8) * S));
+            n_vis = nunit;
+        }
         const bf16_t* q_ = (const bf16_t*)q;
         // the caches are written only by a fused append, whose caller handed them over writable
         bf16_t *k_ = const_cast<bf16_t*>((const bf16_t*)Kp), *v_ = const_cast<bf16_t*>((const bf16_t*)Vc);
@@ -1115,7 +1238,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
     case RV:                                                                                               \
         launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2, ws_m,   \
                                  ws_l, ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta, tx, TS, SP, \
-                                 n_vis);                                                                   \
+                                 n_vis, fused_merge ? (bf16_t*)out : nullptr, counters);                   \
         break;
         switch (keep_padded(r)) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)
@@ -1123,7 +1246,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         }
 #undef RK_CASE
         e = hipGetLastError();
-        if (e != hipSuccess || direct) return e;
+        if (e != hipSuccess || direct || fused_merge) return e;
     } else {
         dim3 grid(S, Hq, B);
         if (dtype == 0)
@@ -1167,6 +1290,31 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
                            app ? app->seq_len : (int32_t*)nullptr, (int32_t*)nullptr, 0);
     }
     return hipGetLastError();
+}
+
+// Every work-group records the id of the XCD it runs on (hardware register XCC_ID, low 4 bits).
+__global__ void xcd_of_workgroup(int32_t* out)
+{
+    uint32_t x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)(x & 15u) + 1;
+}
+
+hipError_t probe_xcd_deal(int32_t* scratch, bool* same_xcd)
+{
+    *same_xcd = false;
+    int32_t h[64];
+    hipLaunchKernelGGL(xcd_of_workgroup, dim3(64), dim3(64), 0, 0, scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipMemcpy(h, scratch, sizeof(h), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return e;
+    e = hipMemset(scratch, 0, sizeof(h));
+    if (e != hipSuccess) return e;
+    bool ok = true;
+    for (int i = 0; i < 64; ++i) ok = ok && h[i] > 0 && h[i] == h[i & 7];
+    *same_xcd = ok;
+    return hipDeviceSynchronize();
 }
 
 hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,

@@ -80,10 +80,18 @@ bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r);
 //                 bumped before the merge kernel reads it; text->max_len must already count the new row
 // tiles_all: 128-token tiles of the longest sequence; split s takes a balanced share of them
 // ws: partials, ((S + DECODE_TEXT_SLICES_MAX) (d + 2) + 1) floats per (b, h_q)
+// counters: n_counters ints that are zero between launches (or null): lets a plain matrix-core decode
+//           fold its partials inside the split launch (one counter per (b, h_kv, head group)).  Only
+//           valid on a device that deals work-groups to its XCDs round-robin by linear index
+//           (probe_xcd_deal)
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
-                         float scale, void* out, float* ws, hipStream_t st);
+                         float scale, void* out, float* ws, int32_t* counters, int n_counters, hipStream_t st);
+// Whether work-groups whose linear indices agree modulo 8 run on the same XCD (true on MI355X in every
+// partition mode).  Launches a tiny kernel that records each work-group's XCD and synchronises;
+// scratch: 64 ints of device memory, left zeroed.
+hipError_t probe_xcd_deal(int32_t* scratch, bool* same_xcd);
 hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,
                               void* kt, void* vt, int64_t sb, int64_t sh, int64_t st_, int32_t* len,
                               hipStream_t st);

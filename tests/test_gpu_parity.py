@@ -264,6 +264,13 @@ DECODE_CASES = [
     ("r128_f32_dense", "f32", 1, 2, 2, 256, None, 128, False, 2),
     # lengths at tile and split edges
     ("edges", "bf16", 6, 4, 2, 1025, [1025, 1024, 1023, 129, 128, 127], 64, False, 0),
+    # a multiple of 8 units and several splits: the merge runs inside the split launch (the unit's last
+    # work-group folds the partials); ragged, empty and one-token sequences, every kernel width class
+    ("merge_in_split_8u", "bf16", 4, 14, 2, 3000, [3000, 1500, 0, 129], 64, False, 0),
+    ("merge_in_split_16u_s7", "bf16", 8, 8, 2, 2000, [2000, 1999, 1, 0, 777, 1024, 1025, 128], 48, False, 7),
+    ("merge_in_split_mha_r96", "bf16", 1, 8, 8, 4096, None, 96, False, 0),
+    ("merge_in_split_s20", "bf16", 2, 28, 4, 2600, [2600, 2047], 37, False, 20),
+    ("merge_in_split_g20", "bf16", 4, 20, 1, 1500, [1500, 640, 3, 1279], 32, False, 3),
 ]
 
 
@@ -280,12 +287,16 @@ def test_decode_parity(ctx, case):
         got = p.decode(q)
         got_nobias = p.decode(q, use_bias=False).copy()
         again = p.decode(q)
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 0)          # the merge as a launch of its own
+        got_two = p.decode(q).copy()
     finally:
         rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
         rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 0)
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 1)
     want = oracle_decode(p, data["q"], lens)
     check_out(got, want, dtype)
     check_out(got_nobias, want, dtype)          # bias = constant shift when all tokens are rotated
+    check_out(got_two, want, dtype)
     assert np.array_equal(got, again)            # fixed merge order: bit-stable
     for b in range(B):
         if lens[b] == 0:
