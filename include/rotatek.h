@@ -161,6 +161,15 @@ size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L);
  * is sized to fill 256 compute units.                                         */
 rk_status rk_decode_plan(const rk_ctx* ctx, const rk_layout* L, int32_t* n_splits, int32_t* tokens_per_split);
 
+/* ---- measurement helper: streaming-read ceiling --------------------------------
+ * Reads `bytes` (a positive multiple of 16) of device memory at `src` (16-byte
+ * aligned) once with plain streaming loads and keeps nothing.  The decode step is
+ * bound by how fast the cache can be streamed from HBM (Sec. 4, "memory IO"); a
+ * benchmark times this call on a buffer of the cache's size to get the rate the
+ * device actually sustains for such a read, next to the datasheet peak.
+ * Errors: INVALID_ARG, NO_DEVICE, HIP.                                          */
+rk_status rk_stream_read(rk_ctx* ctx, const void* src, size_t bytes, void* stream);
+
 /* ---- Alg. 1 steps 1-13 with the full eigendecomposition + keep-mask ---------
  * Per (b, h_kv): mu and the centered scatter C = (K-mu)^T (K-mu) of the rows
  * described by `keys` (Alg. 1 steps 1-3); C_q = (sigma sigma^T) .* C (step 5,

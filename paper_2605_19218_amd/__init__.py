@@ -28,7 +28,7 @@ EXPORTS = [
     "rk_fit_workspace_size", "rk_decode_workspace_size", "rk_decode_plan", "rk_fit_rotation",
     "rk_gather_rotation", "rk_compress", "rk_append", "rk_decode_attn", "rk_cache_bytes", "rk_unpack_cache",
     "rk_decode_attn_dual", "rk_append_text", "rk_fit_subspace", "rk_query_sigma", "rk_append_decode_attn",
-    "rk_append_text_decode_attn_dual", "rk_decode_attn_static",
+    "rk_append_text_decode_attn_dual", "rk_decode_attn_static", "rk_stream_read",
 ]
 RK_STATIC_SCRATCH_BYTES = 8 << 20
 
@@ -100,6 +100,7 @@ def lib():
         L.rk_compress.argtypes = [vp, PL, PR, vp, vp, PR, vp, vp, vp]
         L.rk_append.argtypes = [vp, PL, vp, vp, vp, vp, vp, vp, vp]
         L.rk_decode_attn.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+        L.rk_stream_read.argtypes = [vp, vp, sz, vp]
         L.rk_decode_attn_static.argtypes = [vp, PL, vp, vp, vp, vp, vp, f32, vp, vp]
         L.rk_decode_attn_dual.argtypes = [vp, PL, vp, vp, vp, vp, vp, PT, f32, vp, vp, sz, vp]
         L.rk_append_text.argtypes = [vp, PL, PT, vp, vp, vp]
@@ -294,6 +295,12 @@ def rk_decode_attn(ctx, layout: Layout, q, k_packed, v_cache, R_r, delta_mu, sca
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
     _check(ctx, lib().rk_decode_attn(ctx, C.byref(layout.c()), _ptr(q), _ptr(k_packed), _ptr(v_cache), _ptr(R_r),
                                      _ptr(delta_mu), float(scale), _ptr(out), _ptr(workspace), wb,
+                                     _stream(stream)))
+
+
+def rk_stream_read(ctx, src, nbytes: Optional[int] = None, stream=None) -> None:
+    """Calibration: one plain streaming read of a device buffer."""
+    _check(ctx, lib().rk_stream_read(ctx, _ptr(src), int(nbytes if nbytes is not None else _nbytes(src)),
                                      _stream(stream)))
 
 

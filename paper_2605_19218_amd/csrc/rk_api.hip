@@ -321,6 +321,20 @@ rk_status rk_unpack_cache(rk_ctx* ctx, const rk_layout* L, const void* k_packed,
     return RK_OK;
 }
 
+rk_status rk_stream_read(rk_ctx* ctx, const void* src, size_t bytes, void* stream)
+{
+    if (!ctx) return RK_ERR_INVALID_ARG;
+    if (!src || ((uintptr_t)src & 15) || bytes == 0 || (bytes & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "stream_read: src must be non-NULL and 16-byte aligned, bytes a positive multiple of 16");
+    if (ctx->device == RK_DEVICE_NONE) return fail(ctx, RK_ERR_NO_DEVICE, "valid arguments, but the context has no device");
+    DeviceGuard dev(ctx->device);
+    hipError_t e = dev.status;
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipSetDevice");
+    e = launch_stream_read(src, bytes, ctx->n_cu, nullptr, as_stream(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "stream_read launch");
+    return RK_OK;
+}
+
 rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, const float* sigma,
                           uint32_t flags, const rk_fit_out* out, void* workspace, size_t workspace_bytes,
                           void* stream)

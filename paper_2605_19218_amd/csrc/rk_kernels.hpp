@@ -92,6 +92,8 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
 // partition mode).  Launches a tiny kernel that records each work-group's XCD and synchronises;
 // scratch: 64 ints of device memory, left zeroed.
 hipError_t probe_xcd_deal(int32_t* scratch, bool* same_xcd);
+// plain streaming read of `bytes` (a multiple of 16) of device memory; sink: one writable int (or null)
+hipError_t launch_stream_read(const void* src, size_t bytes, int n_cu, int32_t* sink, hipStream_t st);
 hipError_t launch_append_text(int dtype, int B, int Hkv, int capacity, const void* k_new, const void* v_new,
                               void* kt, void* vt, int64_t sb, int64_t sh, int64_t st_, int32_t* len,
                               hipStream_t st);
