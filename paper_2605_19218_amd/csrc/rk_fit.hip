@@ -435,6 +435,33 @@ __device__ __forceinline__ void rr_pair(int round, int k, int& p, int& q) {
     }
 }
 
+// Rotation that annihilates the (p, q) element: t = tan, s = sin, tau = s / (1 + c).  One square
+// root and hardware reciprocals with a Newton step each: the chain sits between the two barriers of
+// every round, and the IEEE division and square-root sequences are several times as long.
+// (s, tau) is applied as x' = x - s (y + tau x), y' = y + s (x - tau y), which is orthogonal to the
+// accuracy of tau = s / (1 + c) alone, so a last-place error in t only moves the angle.
+__device__ __forceinline__ float rcp_nr(float x)
+{
+    float r = __builtin_amdgcn_rcpf(x);
+    return fmaf(r, fmaf(-x, r, 1.f), r);
+}
+__device__ __forceinline__ void jacobi_params(float app, float aqq, float apq, float thr_skip, float& s, float& tau,
+                                              float& t)
+{
+    s = 0.f; tau = 0.f; t = 0.f;
+    if (fabsf(apq) > thr_skip) {
+        // t = sgn(theta) / (|theta| + sqrt(theta^2 + 1)), theta = (aqq - app) / (2 apq), without forming theta
+        const float al = aqq - app, be = 2.f * apq;
+        const float h = __builtin_amdgcn_sqrtf(fmaf(al, al, be * be));
+        t = (al >= 0.f) ? be * rcp_nr(al + h) : be * rcp_nr(al - h);
+        const float d = fmaf(t, t, 1.f);
+        float c = __builtin_amdgcn_rsqf(d);
+        c = c * fmaf(-0.5f * d * c, c, 1.5f);          // one Newton step on 1/sqrt(d)
+        s = t * c;
+        tau = s * rcp_nr(1.f + c);
+    }
+}
+
 __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restrict__ cov,
                                                           const float* __restrict__ sigma,
                                                           const float* __restrict__ mu_in, int r,
@@ -505,18 +532,11 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
             if (tid < 64) {
                 int p, q;
                 rr_pair(round, tid, p, q);
-                float app = A[p * D + p], aqq = A[q * D + q], apq = A[p * D + q];
                 // Rotations are applied as x' = x - s (y + tau x), y' = y + s (x - tau y) with
                 // tau = s / (1 + c): 1 - c is then carried to relative precision, so small
                 // angles (c rounding to 1) do not inflate the column norms of V.
-                float s = 0.f, tau = 0.f, t = 0.f;
-                if (fabsf(apq) > thr_skip) {
-                    float th = (aqq - app) / (2.f * apq);
-                    t = copysignf(1.f, th) / (fabsf(th) + sqrtf(fmaf(th, th, 1.f)));
-                    float c = 1.f / sqrtf(fmaf(t, t, 1.f));
-                    s = t * c;
-                    tau = s / (1.f + c);
-                }
+                float s, tau, t;
+                jacobi_params(A[p * D + p], A[q * D + q], A[p * D + q], thr_skip, s, tau, t);
                 rs[tid] = s;
                 rtau[tid] = tau;
                 rt[tid] = t;
