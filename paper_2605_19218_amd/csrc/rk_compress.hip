@@ -52,14 +52,14 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
 // operand are permuted so that after output blocks 2i and 2i+1 lane (g, n) holds
 // the 8 output channels 32 i + 8 g ..+7 of token n -- one 16-byte piece of the
 // packed layout, and consecutive lanes write consecutive pieces.
-template <int R>
+template <int R, int NP>
 struct CompressCfg {
     static constexpr int JB = R / 16;                 // 16-wide output-channel blocks
     static constexpr int NF = R / 32;                 // full 32-channel groups
     static constexpr bool TAIL = (R % 32) != 0;       // one trailing 16-channel block
-    static constexpr int TT = (R <= 64) ? 4 : 2;      // 16-token tiles in flight per wave
+    static constexpr int TT = 2;                      // 16-token tiles per wave and pass (two passes in flight)
     static constexpr int TOK_PER_PASS = 4 * TT * 16;  // tokens one pass of the 4 waves covers
-    static constexpr int PASSES = 4;                  // passes per work-group (amortises the R_r fragment build)
+    static constexpr int PASSES = NP;                  // passes per work-group (amortises the R_r fragment build)
     static constexpr int TOK_PER_BLOCK = PASSES * TOK_PER_PASS;
     static constexpr size_t LDS_BYTES = (size_t)JB * 4 * 2 * 64 * 16;   // A fragments, hi+lo
     // output channel held by A row a of block jb
@@ -72,12 +72,12 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
     return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
-template <int R, bool GATHER>
-__global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int cap, int r,
+template <int R, bool GATHER, int NP>
+__global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, int cap, int r,
                                                      const float* __restrict__ Rr, bf16_t* __restrict__ Kp,
                                                      int32_t* __restrict__ seq_len_out)
 {
-    typedef CompressCfg<R> Cfg;
+    typedef CompressCfg<R, NP> Cfg;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16x8* frag = (bf16x8*)smem_raw;       // [JB][4][2][64]
 
@@ -89,58 +89,30 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
     const int blk0 = blockIdx.x * Cfg::TOK_PER_BLOCK;
     if (blk0 >= n_b) return;
 
-    // A fragments: block jb, k-step i, lane (gk, a): row a <-> output channel chan(jb, a);
-    // k slots <-> input channels 32 i + 8 gk + jj.
-    const float* Ru = Rr + (size_t)u * D * r;
-    // EXACT: r is the kernel's own width (the common case), so the row stride of R_r is a compile-time
-    // constant; otherwise r < R and the columns r .. R - 1 are the zero padding
-    auto build = [&](auto exact) {
-        constexpr bool EXACT = decltype(exact)::value;
-        const int rs = EXACT ? R : r;
-        for (int f = tid; f < Cfg::JB * 4 * 64; f += 256) {
-            int l = f & 63, i = (f >> 6) & 3, jb = f >> 8;
-            int gk = l >> 4, a = l & 15;
-            int j = Cfg::chan(jb, a);
-            bf16x8 hi, lo;
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                float x = (EXACT || j < r) ? Ru[(32 * i + 8 * gk + jj) * rs + j] : 0.f;
-                __bf16 xh, xl;
-                split_bf16(x, xh, xl);
-                hi[jj] = xh;
-                lo[jj] = xl;
-            }
-            frag[((jb * 4 + i) * 2 + 0) * 64 + l] = hi;
-            frag[((jb * 4 + i) * 2 + 1) * 64 + l] = lo;
-        }
-    };
-    if (r == R) build(std::true_type{});
-    else build(std::false_type{});
-    __syncthreads();
-
     const bf16_t* base = (const bf16_t*)rows.data;
     const int64_t hb = (int64_t)b * rows.sb + (int64_t)h * rows.sh;
     const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
     bf16_t* Ku = Kp + (size_t)u * cap * R;
 
-    for (int pass = 0; pass < Cfg::PASSES; ++pass) {
-        const int w0 = blk0 + pass * Cfg::TOK_PER_PASS + wave * (Cfg::TT * 16);
-        if (w0 >= n_b) return;                      // later passes start even further right
-
-        bf16x8 kb[Cfg::TT][4];
+    // Key rows of one pass of this wave, straight into B-operand registers.  Every row is read
+    // once: non-temporal.  Rows past the end are clamped to the last row (never stored).
+    auto load_keys = [&](bf16x8 (&kb)[Cfg::TT][4], int w0) {
 #pragma unroll
         for (int tt = 0; tt < Cfg::TT; ++tt) {
-            int tok = min(w0 + tt * 16 + n, n_b - 1);
+            const int tok = min(w0 + tt * 16 + n, n_b - 1);
             const bf16_t* row = base + row_off<GATHER>(hb, rows.st, list, tok);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kb[tt][i] = *(const bf16x8*)(row + 32 * i + 8 * g);
+            for (int i = 0; i < 4; ++i)
+                kb[tt][i] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)(row + 32 * i + 8 * g)));
         }
+    };
+    // rotate one pass and store its packed rows
+    auto rotate_store = [&](const bf16x8 (&kb)[Cfg::TT][4], int w0, auto all_valid) {
         f32x4 acc[Cfg::TT][Cfg::JB];
 #pragma unroll
         for (int tt = 0; tt < Cfg::TT; ++tt)
 #pragma unroll
             for (int jb = 0; jb < Cfg::JB; ++jb) acc[tt][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
 #pragma unroll
         for (int jb = 0; jb < Cfg::JB; ++jb) {
 #pragma unroll
@@ -153,12 +125,14 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
                     acc[tt][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, kb[tt][i], acc[tt][jb], 0, 0, 0);
                 }
             }
+            // the fragment reads of one output block at a time: hoisting all of them costs 128 registers
+            if (Cfg::JB > 4 && (jb & 1)) __builtin_amdgcn_sched_barrier(0);
         }
         // lane (g, n): blocks 2i, 2i+1 hold channels 32 i + 8 g + (0..3), (4..7) of token w0 + 16 tt + n
 #pragma unroll
         for (int tt = 0; tt < Cfg::TT; ++tt) {
             int tok = w0 + tt * 16 + n;
-            if (tok < n_b) {
+            if (decltype(all_valid)::value || tok < n_b) {
                 bf16_t* blk = Ku + (size_t)((w0 >> 4) + tt) * (16 * R);
 #pragma unroll
                 for (int i = 0; i < Cfg::NF; ++i) {
@@ -177,6 +151,85 @@ __global__ __launch_bounds__(256) void compress_mfma(RowsDev rows, int Hkv, int 
                 }
             }
         }
+    };
+
+    // A fragments: block jb, k-step i, lane (gk, a): row a <-> output channel chan(jb, a);
+    // k slots <-> input channels 32 i + 8 gk + jj.  Thread tid builds fragment (jb = it, i = tid / 64,
+    // lane = tid % 64) for it = 0 .. JB - 1: R_r elements first (all loads of a thread in flight
+    // together), the split into bf16 head + remainder after them.
+    const float* Ru = Rr + (size_t)u * D * r;
+    const int fi = tid >> 6, fgk = lane >> 4, fa = lane & 15;
+    float rx[Cfg::JB][8];
+    // EXACT: r is the kernel's own width (the common case), so the row stride of R_r is a compile-time
+    // constant; otherwise r < R and the columns r .. R - 1 are the zero padding
+    auto fetch_Rr = [&](auto exact) {
+        constexpr bool EXACT = decltype(exact)::value;
+        const int rs = EXACT ? R : r;
+#pragma unroll
+        for (int jb = 0; jb < Cfg::JB; ++jb) {
+            const int j = Cfg::chan(jb, fa);
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                rx[jb][jj] = Ru[(32 * fi + 8 * fgk + jj) * rs + (EXACT ? j : min(j, r - 1))];
+        }
+    };
+    auto park_fragments = [&]() {
+#pragma unroll
+        for (int jb = 0; jb < Cfg::JB; ++jb) {
+            const bool pad = Cfg::chan(jb, fa) >= r;
+            bf16x8 hi, lo;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                __bf16 xh, xl;
+                split_bf16(pad ? 0.f : rx[jb][jj], xh, xl);
+                hi[jj] = xh;
+                lo[jj] = xl;
+            }
+            frag[((jb * 4 + fi) * 2 + 0) * 64 + lane] = hi;
+            frag[((jb * 4 + fi) * 2 + 1) * 64 + lane] = lo;
+        }
+    };
+    if (r == R) fetch_Rr(std::true_type{});
+    else fetch_Rr(std::false_type{});
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int w_first = blk0 + wave * (Cfg::TT * 16);
+    if (blk0 + Cfg::TOK_PER_BLOCK <= n_b) {
+        // Full block (the normal case): passes in pairs, the Key rows of pass p + 1 requested
+        // before pass p is rotated, the first pass before R_r is even split -- R_r's loads are
+        // older than the Key loads, so the wait for them does not wait for Keys.  The trip count
+        // is a constant and nothing is loaded conditionally: every wait on a load is exact.
+        static_assert(Cfg::PASSES % 2 == 0 && Cfg::PASSES >= 4, "passes are taken in pairs");
+        constexpr int TP = Cfg::TOK_PER_PASS;
+        bf16x8 ka[Cfg::TT][4], kc[Cfg::TT][4];
+        load_keys(ka, w_first);
+        __builtin_amdgcn_sched_barrier(0);
+        park_fragments();
+        __syncthreads();
+#pragma unroll 1
+        for (int p = 0; p < Cfg::PASSES - 2; p += 2) {
+            load_keys(kc, w_first + (p + 1) * TP);
+            __builtin_amdgcn_sched_barrier(0);
+            rotate_store(ka, w_first + p * TP, std::true_type{});
+            load_keys(ka, w_first + (p + 2) * TP);
+            __builtin_amdgcn_sched_barrier(0);
+            rotate_store(kc, w_first + (p + 1) * TP, std::true_type{});
+        }
+        load_keys(kc, w_first + (Cfg::PASSES - 1) * TP);
+        __builtin_amdgcn_sched_barrier(0);
+        rotate_store(ka, w_first + (Cfg::PASSES - 2) * TP, std::true_type{});
+        rotate_store(kc, w_first + (Cfg::PASSES - 1) * TP, std::true_type{});
+        return;
+    }
+    // ragged last block of a sequence: one pass at a time
+    park_fragments();
+    __syncthreads();
+    for (int pass = 0; pass < Cfg::PASSES; ++pass) {
+        const int w0 = w_first + pass * Cfg::TOK_PER_PASS;
+        if (w0 >= n_b) return;                      // later passes start even further right
+        bf16x8 kb[Cfg::TT][4];
+        load_keys(kb, w0);
+        rotate_store(kb, w0, std::false_type{});
     }
 }
 
@@ -301,20 +354,32 @@ __global__ __launch_bounds__(256) void unpack_cache(int cap, int r, const T* __r
 }
 
 // ---------------------------------------------------------------------------
+template <int R, int NP>
+static hipError_t launch_compress_mfma_rp(const RowsDev& rows, int B, int Hkv, int cap, int r, const float* Rr,
+                                          bf16_t* Kp, int32_t* seq_len_out, hipStream_t st)
+{
+    typedef CompressCfg<R, NP> Cfg;
+    int nblk = (rows.n_tokens + Cfg::TOK_PER_BLOCK - 1) / Cfg::TOK_PER_BLOCK;
+    if (nblk < 1) nblk = 1;
+    if (rows.tok_idx)
+        hipLaunchKernelGGL((compress_mfma<R, true, NP>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
+                           cap, r, Rr, Kp, seq_len_out);
+    else
+        hipLaunchKernelGGL((compress_mfma<R, false, NP>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
+                           cap, r, Rr, Kp, seq_len_out);
+    return hipGetLastError();
+}
+
+// 2048 tokens per work-group (one R_r fragment build per 2048 rows, one work-group per compute unit at
+// the large shapes) when that still gives every one of the 256 compute units a work-group, else 512
 template <int R>
 static hipError_t launch_compress_mfma_r(const RowsDev& rows, int B, int Hkv, int cap, int r, const float* Rr,
                                          bf16_t* Kp, int32_t* seq_len_out, hipStream_t st)
 {
-    typedef CompressCfg<R> Cfg;
-    int nblk = (rows.n_tokens + Cfg::TOK_PER_BLOCK - 1) / Cfg::TOK_PER_BLOCK;
-    if (nblk < 1) nblk = 1;
-    if (rows.tok_idx)
-        hipLaunchKernelGGL((compress_mfma<R, true>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
-                           cap, r, Rr, Kp, seq_len_out);
-    else
-        hipLaunchKernelGGL((compress_mfma<R, false>), dim3(nblk, Hkv, B), dim3(256), Cfg::LDS_BYTES, st, rows, Hkv,
-                           cap, r, Rr, Kp, seq_len_out);
-    return hipGetLastError();
+    const int64_t long_blocks = (int64_t)((rows.n_tokens + CompressCfg<R, 16>::TOK_PER_BLOCK - 1) /
+                                          CompressCfg<R, 16>::TOK_PER_BLOCK) * Hkv * B;
+    if (long_blocks >= 256) return launch_compress_mfma_rp<R, 16>(rows, B, Hkv, cap, r, Rr, Kp, seq_len_out, st);
+    return launch_compress_mfma_rp<R, 4>(rows, B, Hkv, cap, r, Rr, Kp, seq_len_out, st);
 }
 
 hipError_t launch_compress(int dtype, bool mfma, const RowsDev& rows, int B, int Hkv, int cap, int r,

@@ -102,11 +102,11 @@ __global__ __launch_bounds__(256) void cov_partial_generic(RowsDev rows, int Hkv
 // therefore ch(cbk, m) = 8 (m % 16) + 2 cbk + m / 16 -- a permutation that is undone
 // when the 128x128 partial is written.  Each wave accumulates the 10 upper-triangular
 // 32x32 tiles for its own 512 tokens (160 accumulator registers); the four waves are
-// summed through LDS in a fixed order.
+// summed through LDS in a fixed order, each wave folding and storing a quarter.
 constexpr int COVM_TOK_PER_WAVE = 512;
 constexpr int COVM_CHUNK = 4 * COVM_TOK_PER_WAVE;
-constexpr int COVM_STAGES = 6;             // 16-token k-steps of loads in flight per wave
-constexpr size_t COVM_LDS_BYTES = (size_t)(2 * 10 * 16 * 64 + 4 * D) * sizeof(float);   // 2 parked sets + column sums
+constexpr int COVM_STAGES = 4;             // 16-token k-steps of loads in flight per wave (16 KB; 3 to 5 time alike, 6 and 8 slower)
+constexpr size_t COVM_LDS_BYTES = (size_t)(4 * 30 * 4 * 64 + 4 * D) * sizeof(float);   // 4 x 30 parked groups + column sums
 
 // rows >= t_end contribute zeros; the address is clamped to row t_last (always a valid row)
 // all 8 rows known to be valid: plain loads, nothing for the compiler to predicate.  Without
@@ -120,7 +120,11 @@ __device__ __forceinline__ void covm_load_full(uint4 (&r)[8], const bf16_t* __re
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj) {
         if (GATHER) r[jj] = *(const uint4*)(base + row_off<true>(head_base, st, list, tok0 + jj) + 8 * o);
-        else r[jj] = *(const uint4*)(lane_ptr + (int64_t)(tok_rel + jj) * st);
+        else {
+            // read-once stream: non-temporal, so the rows do not displace each other in the L2
+            const u32x4 v = __builtin_nontemporal_load((const u32x4*)(lane_ptr + (int64_t)(tok_rel + jj) * st));
+            r[jj] = make_uint4(v.x, v.y, v.z, v.w);
+        }
     }
 }
 
@@ -170,6 +174,45 @@ __device__ __forceinline__ void covm_step(const uint4 (&r)[8], uint32_t sel, f32
         }
 }
 
+// End-of-chunk reduction over the four waves of a work-group.  park area: [wave][30][lane]
+// 16-byte groups, wave w's group g (not one of its own) at slot g - (g > 10 w ? 10 : 0).
+constexpr int COVM_OWN = 10, COVM_PARKED = 30;
+__device__ __forceinline__ constexpr int covm_slot(int w, int g) { return w * COVM_PARKED + (g < COVM_OWN * w ? g : g - COVM_OWN); }
+
+template <int W>
+__device__ __forceinline__ void covm_park(const f32x16 (&acc)[10], f32x4* __restrict__ park, int lane)
+{
+#pragma unroll
+    for (int g = 0; g < 40; ++g)
+        if (g / COVM_OWN != W)
+            park[covm_slot(W, g) * 64 + lane] =
+                (f32x4){acc[g >> 2][4 * (g & 3)], acc[g >> 2][4 * (g & 3) + 1], acc[g >> 2][4 * (g & 3) + 2], acc[g >> 2][4 * (g & 3) + 3]};
+}
+
+// partial layout written here: [g][lane][4] floats (element e of group g is accumulator
+// i = 4 (g % 4) + e of tile g / 4)
+template <int W>
+__device__ __forceinline__ void covm_fold_store(const f32x16 (&acc)[10], const f32x4* __restrict__ park, int lane,
+                                                f32x4* __restrict__ S4)
+{
+    f32x4 p[4][COVM_OWN];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int k = 0; k < COVM_OWN; ++k) {
+            const int g = COVM_OWN * W + k;
+            if (w == W) p[w][k] = (f32x4){acc[g >> 2][4 * (g & 3)], acc[g >> 2][4 * (g & 3) + 1], acc[g >> 2][4 * (g & 3) + 2], acc[g >> 2][4 * (g & 3) + 3]};
+            else p[w][k] = park[covm_slot(w, g) * 64 + lane];
+        }
+#pragma unroll
+    for (int k = 0; k < COVM_OWN; ++k) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = ((p[0][k][e] + p[1][k][e]) + p[2][k][e]) + p[3][k][e];
+        S4[(COVM_OWN * W + k) * 64 + lane] = v;
+    }
+}
+
 template <bool GATHER>
 __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, int n_chunks,
                                                         float* __restrict__ part_S, float* __restrict__ part_sum)
@@ -192,8 +235,8 @@ __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, i
     const bf16_t* lane_ptr = base + hb + (int64_t)(tw0 + 8 * g2) * rst + 8 * o;
 
     extern __shared__ __attribute__((aligned(16))) float cov_smem[];
-    f32x4* bufv = (f32x4*)cov_smem;             // two parked accumulator sets: [2][tile][i / 4][lane]
-    float (*ssum)[D] = (float (*)[D])(cov_smem + 2 * 10 * 16 * 64);
+    f32x4* bufv = (f32x4*)cov_smem;             // parked accumulator groups: [wave][30][lane]
+    float (*ssum)[D] = (float (*)[D])(cov_smem + 4 * 30 * 4 * 64);
 
     f32x16 acc[10];
 #pragma unroll
@@ -254,51 +297,30 @@ __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, i
     }
 
 #undef KSTEP_TOK
-
-    // ---- sum the four waves in a fixed order: ((w0 + w1) + w2) + w3 --------------------
+    // ---- sum the four waves, every element as ((w0 + w1) + w2) + w3 ----------------------
+    // The 160 accumulators of a lane form 40 groups of four, g = 4 tile + i / 4.  Wave w owns
+    // groups [10 w, 10 w + 10): it parks the 30 groups it does not own, and after ONE barrier
+    // adds the three parked copies of its own groups to its registers (all 30 reads issued
+    // before the first add) and stores its quarter of the chunk's partial, 16 bytes per lane.
 #pragma unroll
     for (int cbk = 0; cbk < 4; ++cbk) {
         float s = csum[cbk] + __shfl_xor(csum[cbk], 32);
         if (g2 == 0) ssum[wave][8 * o + 2 * cbk + par] = s;
     }
-    // (w0 + w1) + (w2 + w3), two phases, 128-bit LDS traffic
-    auto park = [&](int set) {
-#pragma unroll
-        for (int t = 0; t < 10; ++t)
-#pragma unroll
-            for (int iq = 0; iq < 4; ++iq)
-                bufv[(set * 40 + t * 4 + iq) * 64 + lane] =
-                    (f32x4){acc[t][4 * iq], acc[t][4 * iq + 1], acc[t][4 * iq + 2], acc[t][4 * iq + 3]};
-    };
-    auto add = [&](int set) {
-#pragma unroll
-        for (int t = 0; t < 10; ++t)
-#pragma unroll
-            for (int iq = 0; iq < 4; ++iq) {
-                const f32x4 v = bufv[(set * 40 + t * 4 + iq) * 64 + lane];
-                acc[t][4 * iq] += v[0]; acc[t][4 * iq + 1] += v[1]; acc[t][4 * iq + 2] += v[2]; acc[t][4 * iq + 3] += v[3];
-            }
-    };
-    if (wave == 1) park(0);
-    if (wave == 3) park(1);
-    __syncthreads();
-    if (wave == 0) add(0);
-    if (wave == 2) add(1);
-    __syncthreads();
-    if (wave == 2) park(0);
-    __syncthreads();
-    // wave 0 holds the chunk's sum; it stores the 10 upper-triangular tiles in register layout
-    // ([tile][i][lane], 40 KB, fully coalesced).  cov_finalize undoes the channel permutation
-    // and mirrors the lower triangle while it reduces over chunks.
-    if (wave == 0) {
-        add(0);
-        float* S = part_S + ((size_t)u * n_chunks + chunk) * (D * D);
-#pragma unroll
-        for (int t = 0; t < 10; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) S[(t * 16 + i) * 64 + lane] = acc[t][i];
+    switch (wave) {
+    case 0: covm_park<0>(acc, bufv, lane); break;
+    case 1: covm_park<1>(acc, bufv, lane); break;
+    case 2: covm_park<2>(acc, bufv, lane); break;
+    default: covm_park<3>(acc, bufv, lane); break;
     }
     __syncthreads();
+    f32x4* S4 = (f32x4*)(part_S + ((size_t)u * n_chunks + chunk) * (D * D));
+    switch (wave) {
+    case 0: covm_fold_store<0>(acc, bufv, lane, S4); break;
+    case 1: covm_fold_store<1>(acc, bufv, lane, S4); break;
+    case 2: covm_fold_store<2>(acc, bufv, lane, S4); break;
+    default: covm_fold_store<3>(acc, bufv, lane, S4); break;
+    }
     if (tid < D)
         part_sum[((size_t)u * n_chunks + chunk) * D + tid] = ((ssum[0][tid] + ssum[1][tid]) + ssum[2][tid]) + ssum[3][tid];
 }
@@ -307,19 +329,7 @@ __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, i
 // Reduce the chunk partials in fp64 and apply the centering correction
 // C = S - n mu mu^T (equal to (K-mu)^T (K-mu)).  grid (8, U): block x covers rows
 // [16x, 16x+16).
-// position of element (row channel, column channel) inside a tile-format partial written by
-// cov_partial_mfma: the 10 upper-triangular 32x32 MFMA tiles as [tile][i][lane]
-__device__ __forceinline__ int covm_tile_index(int rch, int cch)
-{
-    int br = (rch & 7) >> 1, mr = (rch >> 3) + 16 * (rch & 1);
-    int bc = (cch & 7) >> 1, mc = (cch >> 3) + 16 * (cch & 1);
-    if (br > bc) { int x = br; br = bc; bc = x; x = mr; mr = mc; mc = x; }
-    const int t = br * 4 - (br * (br - 1)) / 2 + (bc - br);
-    const int i = 4 * (mr >> 3) + (mr & 3), gg = (mr >> 2) & 1;
-    return (t * 16 + i) * 64 + 32 * gg + mc;
-}
-
-__global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n_chunks, int center, int tiled,
+__global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n_chunks, int center,
                                                     const float* __restrict__ part_S,
                                                     const float* __restrict__ part_sum,
                                                     float* __restrict__ cov, float* __restrict__ mu_out)
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(256) void cov_finalize(RowsDev rows, int Hkv, int n
     const int j = tid & (D - 1);
     for (int ri = 0; ri < 8; ++ri) {
         int i = blockIdx.x * 16 + ri * 2 + (tid >> 7);
-        const int pos = tiled ? covm_tile_index(i, j) : i * D + j;
+        const int pos = i * D + j;
         double s = chunk_sum(part_S + (size_t)u * n_chunks * (D * D) + pos, (size_t)D * D);
         if (center) s -= (double)n_b * (smu[i] * smu[j]);
         cov[(size_t)u * D * D + i * D + j] = (float)s;
@@ -373,7 +383,7 @@ __global__ __launch_bounds__(256) void cov_finalize_tiled(RowsDev rows, int Hkv,
     const int tid = threadIdx.x;
     const int n_b = rows_count(rows, b);
     __shared__ double smu[D];
-    const int posn = blockIdx.x * 256 + tid;            // [tile][i][lane], 0 .. 10239
+    const int posn = blockIdx.x * 256 + tid;            // [tile][i / 4][lane][i % 4], 0 .. 10239
     const float* pS = part_S + (size_t)u * n_chunks * (D * D) + posn;
     // the first 8 chunks of this position: requested before the mean is formed
     float v0[8];
@@ -400,8 +410,8 @@ __global__ __launch_bounds__(256) void cov_finalize_tiled(RowsDev rows, int Hkv,
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc += ch + k < n_chunks ? (double)v[k] : 0.0;
     }
-    // inverse of covm_tile_index
-    const int t = posn >> 10, i = (posn >> 6) & 15, lane = posn & 63;
+    // position -> (row channel, column channel): the MFMA output layout and the channel permutation undone
+    const int t = posn >> 10, i = 4 * ((posn >> 8) & 3) + (posn & 3), lane = (posn >> 2) & 63;
     int br = 0, rem = t;
     while (rem >= 4 - br) { rem -= 4 - br; ++br; }
     const int bc = br + rem;
@@ -687,7 +697,7 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
                            center ? 1 : 0, part_S, part_sum, cov, mu);
     else
         hipLaunchKernelGGL(cov_finalize, dim3(8, B * Hkv), dim3(256), 0, st, rows, Hkv, n_chunks, center ? 1 : 0,
-                           0, part_S, part_sum, cov, mu);
+                           part_S, part_sum, cov, mu);
     return hipGetLastError();
 }
 

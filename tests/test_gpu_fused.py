@@ -8,7 +8,7 @@ import paper_2605_19218_amd as rk
 
 from gpu_util import DEV, Pipeline, bf16_ulp, to_dev, to_host
 from test_gpu_dual import TextSeg, decode_dual, oracle_dual
-from test_gpu_parity import check_out, check_packed, layer, oracle_decode, run_prefill
+from test_gpu_parity import KT_ABS, check_out, check_packed, layer, oracle_decode, run_prefill
 
 pytestmark = pytest.mark.gpu
 
@@ -73,9 +73,11 @@ def test_append_decode_fused(ctx, case):
                     row = Kt[b, h, lens[b]:lens[b] + 1]
                     check_packed(row, new["k_new"][b, h][None].astype(np.float64), Rr[b, h], dtype)
                     assert np.array_equal(Vc[b, h, lens[b]], new["v_new"][b, h].astype(np.float64))
-                    # the same row as rk_append's, up to one unit in the last place
+                    # the same row as rk_append's: one storage ulp plus twice the fp32 accumulation bound
+                    # (an entry that nearly cancels is small against the row norm, not against its own ulp)
                     ref_row = Kt_ref[b, h, lens[b]:lens[b] + 1]
                     tol = bf16_ulp(ref_row) if dtype == "bf16" else 1e-5 * np.abs(ref_row).max()
+                    tol = tol + 2 * KT_ABS * np.linalg.norm(new["k_new"][b, h].astype(np.float64))
                     assert np.all(np.abs(row - ref_row) <= tol)
                     # the prefill rows are untouched
                     assert np.array_equal(Kt[b, h, :lengths[b]], Kt_ref[b, h, :lengths[b]])
