@@ -837,7 +837,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
     constexpr int NCOL = 4 * KB;                          // elimination: columns per thread (4 apart)
     const int kpad = 4 * NCOL;
 
-    const int u = blockIdx.x, tid = threadIdx.x;
+    const int u = blockIdx.x, tid0 = threadIdx.x, tid = tid0;
     const float* C = cov + (size_t)u * D * D;
     const bool weighted = sigma != nullptr;
 
@@ -852,9 +852,14 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
     if (tid < D) sig[tid] = weighted ? (double)sigma[(size_t)u * D + tid] : 1.0;
     __syncthreads();
 
-    const int ib = tid >> 5, jb = tid & 31;               // GEMM tile: rows 4 ib .. +3, columns jb + 32 c
     int fail = 0;
     for (int t = 0; t < T; ++t) {
+        // The thread index is made opaque once per iteration and per phase: otherwise every address and
+        // mask derived from it (a few dozen) is computed before the loop, held in registers through all
+        // phases, and spilled.
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        int ib = tid >> 5, jb = tid & 31;                  // GEMM tile: rows 4 ib .. +3, columns jb + 32 c
         // ---- W <- C_q W ----
         if (weighted) {
             for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
@@ -934,7 +939,8 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
 
         // ---- elimination of [W; G] with the rows in registers, one barrier per column ----
         {
-            const int row = tid >> 2, part = tid & 3;      // stacked row: W rows 0..127, then G rows
+            asm volatile("" : "+v"(tid));
+            int row = tid >> 2, part = tid & 3;            // stacked row: W rows 0..127, then G rows
             const int kp4 = (k + 3) & ~3;                  // G padded with an identity block to a multiple of 4
             double x[NCOL];
 #pragma unroll
@@ -956,6 +962,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
             __syncthreads();                               // piv complete
             if (tid < k) tv[tid] = 1.0 / sqrt(piv[tid]);
             __syncthreads();
+            asm volatile("" : "+v"(row), "+v"(part), "+v"(tid));      // recompute the column numbers: keeping them costs NCOL registers
             if (row < D) {
 #pragma unroll
                 for (int c = 0; c < NCOL; ++c) {
