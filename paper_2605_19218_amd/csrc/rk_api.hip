@@ -94,15 +94,20 @@ RowsDev to_dev(const rk_rows* r)
 
 int cov_chunks(int max_tokens) { int n = (max_tokens + COV_CHUNK - 1) / COV_CHUNK; return n < 1 ? 1 : n; }
 
-struct FitWs { size_t part_S, part_sum, cov, total; };
+// The covariance partials are dead once the covariance is reduced: the eigensolver's recorded
+// rotations reuse their space (the region is sized for the larger of the two).
+struct FitWs { size_t part_S, part_sum, cov, sweeps, total; };
 FitWs fit_ws(const rk_layout* L, int max_tokens)
 {
     size_t U = (size_t)L->batch * L->n_kv_heads, nc = (size_t)cov_chunks(max_tokens);
     FitWs w;
     w.part_S = 0;
-    w.part_sum = align_up(w.part_S + U * nc * D * D * sizeof(float), 256);
+    size_t first = U * nc * D * D * sizeof(float);
+    if (first < eig_rotation_bytes((int)U)) first = eig_rotation_bytes((int)U);
+    w.part_sum = align_up(w.part_S + first, 256);
     w.cov = align_up(w.part_sum + U * nc * D * sizeof(float), 256);
-    w.total = align_up(w.cov + U * D * D * sizeof(float), 256);
+    w.sweeps = align_up(w.cov + U * D * D * sizeof(float), 256);
+    w.total = align_up(w.sweeps + U * sizeof(int32_t), 256);
     return w;
 }
 
@@ -371,7 +376,7 @@ rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys, 
                             part_S, part_sum, cov, out->mu, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "covariance reduction launch");
     e = launch_eig(U, cov, sigma, out->mu, L->keep, out->R, out->eigvals, out->mask, out->keep_idx, out->R_r,
-                   out->delta_mu, out->sweeps, st);
+                   out->delta_mu, out->sweeps, ws + w.part_S, (int32_t*)(ws + w.sweeps), st);
     if (e != hipSuccess) return hip_fail(ctx, e, "eigensolver launch");
     return RK_OK;
 }

@@ -425,24 +425,45 @@ __global__ __launch_bounds__(256) void cov_finalize_tiled(RowsDev rows, int Hkv,
 }
 
 // ---------------------------------------------------------------------------
-// Batched symmetric eigensolver: one 1024-thread work-group per 128x128 matrix,
-// A and the accumulated eigenvectors V both resident in LDS (2 x 64 KB).
-// Parallel two-sided Jacobi with the round-robin ("circle") ordering: a sweep is
-// 127 rounds of 64 disjoint (p, q) pairs.  In a round, thread (k, k') owns the
-// 2x2 block A[{p_k,q_k}][{p_k',q_k'}] and applies J_k^T (.) J_k' to it, so row and
-// column rotations fuse into one pass with no read/write overlap between threads.
-// Columns never move: eigenvalue c is the final A[c][c] and its vector is V[:, c].
+// Batched symmetric eigensolver: parallel two-sided Jacobi with a round-robin ordering (a sweep is
+// 127 rounds of 64 disjoint pairs), in three launches.
+//   eig_jacobi_rotations  one 1024-thread work-group per 128x128 matrix iterates on A alone and
+//                         records the 64 rotations (sin, sin / (1 + cos)) of every round;
+//   eig_apply_rotations   replays the recorded rotations on V = I.  Rows of V are independent, so
+//                         this half of the arithmetic leaves the one compute unit that holds A and
+//                         spreads over the chip, four rows per wave, in registers;
+//   eig_finish            gathers R_r and forms delta_mu.
+// Pairs are taken by POSITION: position 2 k and 2 k + 1 form pair k, and after every round the rows
+// and columns move to new positions (position 0 stays, 1 -> 2, even positions move up by two,
+// 126 -> 127, odd positions move down by two): the 127 moving positions form one cycle, every two
+// indices meet exactly once in 127 rounds, and after a sweep every index is back where it started,
+// so eigenvalue c is the final A[c][c] and its vector is V[:, c].  Because the pairing is fixed in
+// position space, every thread reads and writes the same LDS addresses in every round: the rotated
+// 2x2 block is written straight to its next position in a second copy of A (two copies, row stride
+// 130 floats), there is no index arithmetic in the loop, and only the part of A on or above the
+// diagonal (by pair, then by position) is kept: a rotated element is stored once, at (r, c) or (c, r),
+// whichever lies there.  The LDS pipeline is the bound of a round (about five cycles per wave-wide
+// instruction, whatever its width up to 8 bytes per lane), so the loop is written for few LDS
+// instructions: 7 per block.
 constexpr int EIG_THREADS = 1024;
 constexpr int EIG_MAX_SWEEPS = 20;
-constexpr size_t EIG_LDS_BYTES = (size_t)(2 * D * D + 3 * 64 + 2 * D + 64) * sizeof(float) + D * sizeof(int);
+constexpr int EIG_ROUNDS = D - 1;
+constexpr int EIG_LD = D + 2;             // row stride of the LDS copies of A (even: a 2x2 block is two 8-byte reads)
+constexpr int EIG_ROT_ROUNDS = EIG_MAX_SWEEPS * EIG_ROUNDS;     // recorded rounds per matrix
+constexpr size_t EIG_LDS_BYTES = (size_t)(2 * D * EIG_LD + 4 * 64 + 32 + D) * sizeof(float);
 
-__device__ __forceinline__ void rr_pair(int round, int k, int& p, int& q) {
-    // circle method on n-1 = 127 rotating players, player 127 fixed
-    if (k == 0) { p = D - 1; q = round; }
-    else {
-        p = round + k;       if (p >= D - 1) p -= D - 1;
-        q = round - k;       if (q < 0) q += D - 1;
-    }
+// LDS offset of the kept copy of element (r, c) = (c, r): pairs in ascending order, then positions
+__device__ __forceinline__ constexpr int eig_upper(int r, int c)
+{
+    return ((r >> 1) < (c >> 1) || ((r >> 1) == (c >> 1) && r <= c)) ? r * (D + 2) + c : c * (D + 2) + r;
+}
+
+size_t eig_rotation_bytes(int U) { return (size_t)U * EIG_ROT_ROUNDS * 64 * sizeof(float2); }
+
+// position of a row / column after one round
+__host__ __device__ constexpr int eig_next_pos(int p)
+{
+    return p == 0 ? 0 : p == 1 ? 2 : p == D - 2 ? D - 1 : (p & 1) ? p - 2 : p + 2;
 }
 
 // Rotation that annihilates the (p, q) element: t = tan, s = sin, tau = s / (1 + c).  One square
@@ -472,42 +493,51 @@ __device__ __forceinline__ void jacobi_params(float app, float aqq, float apq, f
     }
 }
 
-__global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restrict__ cov,
-                                                          const float* __restrict__ sigma,
-                                                          const float* __restrict__ mu_in, int r,
-                                                          float* __restrict__ R_out, float* __restrict__ lam_out,
-                                                          uint8_t* __restrict__ mask_out,
-                                                          int32_t* __restrict__ keep_out,
-                                                          float* __restrict__ Rr_out, float* __restrict__ dmu_out,
-                                                          int32_t* __restrict__ sweeps_out)
+constexpr int EIGV_ROWS = 4;
+__device__ __forceinline__ float lane_from_below(float keep, float v)      // lane i <- lane i - 1; lane 0 keeps `keep`
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, v),
+                                                                 0x138, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_from_above(float keep, float v)      // lane i <- lane i + 1; lane 63 keeps `keep`
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, v),
+                                                                 0x130, 0xf, 0xf, false));
+}
+
+template <bool B>
+struct EigBool { static constexpr bool value = B; };
+
+__global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float* __restrict__ cov,
+                                                                    const float* __restrict__ sigma, int r,
+                                                                    float* __restrict__ lam_out,
+                                                                    uint8_t* __restrict__ mask_out,
+                                                                    int32_t* __restrict__ keep_out,
+                                                                    float2* __restrict__ rot,
+                                                                    int32_t* __restrict__ sweeps_ws,
+                                                                    int32_t* __restrict__ sweeps_out)
 {
     extern __shared__ float sm[];
-    float* A = sm;                        // [128][128]
-    float* V = A + D * D;                 // [128][128]
-    float* rs = V + D * D;                // [64] sin
-    float* rtau = rs + 64;                // [64] sin / (1 + cos)
-    float* rt = rtau + 64;                // [64] tan
-    float* slam = rt + 64;                // [128]
-    float* sw = slam + D;                 // [128] scratch (R_r^T mu)
-    float* red = sw + D;                  // [64] reduction scratch
-    int* skeep = (int*)(red + 64);        // [128]
+    float* A2 = sm;                                   // [2][128][129]: the two copies of A
+    float2* prm = (float2*)(A2 + 2 * D * EIG_LD);     // [2][64] (sin, sin / (1 + cos)) of this round and the next
+    float* red = (float*)(prm + 128);                 // [32] reduction scratch
+    float* slam = red + 32;                           // [128]
+    constexpr int BUF = D * EIG_LD;
 
     const int u = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
-    // wave-uniform (scalar registers): the pair indices and row offsets of a wave's blocks are then
-    // computed once per wave on the scalar unit instead of once per lane
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // 16 waves
     const float* C = cov + (size_t)u * D * D;
     const float* sg = sigma ? sigma + (size_t)u * D : nullptr;
+    float2* rot_u = rot + (size_t)u * EIG_ROT_ROUNDS * 64;
 
-    // load C_q = sigma_i sigma_j C_ij, V = I, and ||C_q||_F^2
+    // load C_q = sigma_i sigma_j C_ij and ||C_q||_F^2
     float nrm = 0.f;
     for (int idx = tid; idx < D * D; idx += EIG_THREADS) {
         int i = idx >> 7, j = idx & 127;
         float v = C[idx];
         if (sg) v *= sg[i] * sg[j];
-        A[idx] = v;
-        V[idx] = (i == j) ? 1.f : 0.f;
+        A2[i * EIG_LD + j] = v;
         nrm = fmaf(v, v, nrm);
     }
     nrm = wave_sum(nrm);
@@ -520,14 +550,139 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
     const float tol2 = (2e-8f * 2e-8f) * normF2;
     __syncthreads();
 
+    // The 2016 blocks above the diagonal as 32 wave-wide tasks, two per wave: task j covers row
+    // pair j (63 - j blocks) in its first lanes and row pair 62 - j (j + 1 blocks) in the rest;
+    // task 31 is the 32 blocks of row pair 31 alone.  A thread's two blocks never change.
+    // Stores: one instruction stores an even column from lanes with bit 4 clear and an odd column from
+    // the others (and the second instruction the other way round), so that the 32 lanes the LDS serves
+    // together spread over all 32 banks instead of the 16 of one column parity.
+    const bool hi16 = (lane & 16) != 0;
+    int rd[2], pk[2], pkp[2], wa[2][2], wb[2][2];
+    bool act[2];
+#pragma unroll
+    for (int ts = 0; ts < 2; ++ts) {
+        const int j = ts == 0 ? wave : 31 - wave;
+        const int split = 63 - j;
+        const int k = lane < split ? j : 62 - j;
+        const int kp = lane < split ? j + 1 + lane : 63 - j + (lane - split);
+        act[ts] = !(j == 31 && lane >= 32);
+        rd[ts] = 2 * k * EIG_LD + 2 * kp;
+        pk[ts] = k;
+        pkp[ts] = kp;
+        const int r0 = eig_next_pos(2 * k), r1 = eig_next_pos(2 * k + 1);
+        const int c0 = eig_next_pos(2 * kp), c1 = eig_next_pos(2 * kp + 1);
+        // pairs (x0, x1) = (e00, e01) and (e10, e11): first store takes x0 in the low lanes and x1 in the
+        // high lanes, second store the rest
+        const int w00 = eig_upper(r0, c0), w01 = eig_upper(r0, c1), w10 = eig_upper(r1, c0), w11 = eig_upper(r1, c1);
+        wa[ts][0] = hi16 ? w01 : w00; wb[ts][0] = hi16 ? w00 : w01;
+        wa[ts][1] = hi16 ? w11 : w10; wb[ts][1] = hi16 ? w10 : w11;
+    }
+    // Wave 0, lane k, owns pair k: its diagonal block and its rotation.  The rotation of round n + 1 is
+    // computed DURING round n, so that no wave ever waits for it: after round n the new diagonal
+    // block of pair k holds the old (rotated) diagonal elements of pairs k - 1 and k + 1 -- known to
+    // this wave -- and one off-diagonal element of the block (k - 1, k + 1), which the lane rotates
+    // for itself from the current copy of A (lanes 0, 1 and 63 sit at the ends of the cycle and take
+    // their three elements from the neighbouring places instead).
+    const int lk = lane;
+    const int lrow = lk <= 1 ? 0 : lk == 63 ? 62 : lk - 1;              // row pair of the look-ahead block
+    const int lcol = lk == 0 ? 1 : lk == 63 ? 63 : lk + 1;              // its column pair
+    const int lrd = 2 * lrow * EIG_LD + 2 * lcol;
+    const int dn0 = eig_next_pos(2 * lk), dn1 = eig_next_pos(2 * lk + 1);
+    float ps = 0.f, ptau = 0.f, dE00 = 0.f, dE11 = 0.f, dOff = 0.f;    // pair k: rotation and rotated diagonal block
+    if (wave == 0) {
+        const int dg = 2 * lk * EIG_LD + 2 * lk;
+        const float app = A2[dg], apq = A2[dg + 1], aqq = A2[dg + EIG_LD + 1];
+        float tn;
+        jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
+        prm[lk] = make_float2(ps, ptau);
+        rot_u[lk] = make_float2(ps, ptau);
+        dOff = (ps == 0.f) ? apq : 0.f;                    // left as it is when the rotation is skipped
+        dE00 = app - tn * apq;
+        dE11 = aqq + tn * apq;
+    }
+    __syncthreads();
+
+    // One round: from copy FROM1 of A to the other one; rotations of this round in prm[FROM1].
+    // Rotations are applied as x' = x - s (y + tau x), y' = y + s (x - tau y) with tau = s / (1 + c):
+    // 1 - c is then carried to relative precision, so small angles (c rounding to 1) do not inflate
+    // the column norms of V.
+    auto round_step = [&](auto from1, int t) {
+        constexpr int F = decltype(from1)::value ? 1 : 0;
+        const float* cur = A2 + F * BUF;
+        float* nxt = A2 + (1 - F) * BUF;
+        const float2* pcur = prm + 64 * F;
+        float2* pnext = prm + 64 * (1 - F);
+        if (wave == 0) {
+            // this round's rotated diagonal blocks, at their next positions
+            nxt[dn0 * EIG_LD + dn0] = dE00;
+            nxt[dn1 * EIG_LD + dn1] = dE11;
+            nxt[eig_upper(dn0, dn1)] = dOff;
+            // next round's pair k
+            const float2 ltop = *(const float2*)(cur + lrd), lbot = *(const float2*)(cur + lrd + EIG_LD);
+            const float a00 = ltop.x, a01 = ltop.y, a10 = lbot.x, a11 = lbot.y;
+            const float s1 = lane_from_below(ps, ps), tau1 = lane_from_below(ptau, ptau);      // pair k - 1 (lane 0: its own)
+            const float s2 = lane_from_above(ps, ps), tau2 = lane_from_above(ptau, ptau);      // pair k + 1 (lane 63: its own)
+            const float b00 = a00 - s1 * (a10 + tau1 * a00), b01 = a01 - s1 * (a11 + tau1 * a01);
+            const float b10 = a10 + s1 * (a00 - tau1 * a10), b11 = a11 + s1 * (a01 - tau1 * a11);
+            const float e00 = b00 - s2 * (b01 + tau2 * b00), e01 = b01 + s2 * (b00 - tau2 * b01);
+            const float e11 = b11 + s2 * (b10 - tau2 * b11);
+            const float apq = lk == 1 ? e11 : lk == 63 ? e00 : e01;
+            const float below00 = lane_from_below(dE00, dE00), below11 = lane_from_below(dE11, dE11);
+            const float app = lk == 1 ? below11 : below00;                 // lane 0: its own dE00
+            const float aqq = lane_from_above(dE00, dE11);                 // lane 63: its own dE00
+            float tn;
+            jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
+            pnext[lk] = make_float2(ps, ptau);
+            if (t + 1 < EIG_ROT_ROUNDS) rot_u[(size_t)(t + 1) * 64 + lk] = make_float2(ps, ptau);
+            dOff = (ps == 0.f) ? apq : 0.f;
+            dE00 = app - tn * apq;
+            dE11 = aqq + tn * apq;
+        }
+        float a[2][4];
+        float2 p1[2], p2[2];
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) {
+            const float2 top = *(const float2*)(cur + rd[ts]), bot = *(const float2*)(cur + rd[ts] + EIG_LD);
+            a[ts][0] = top.x; a[ts][1] = top.y; a[ts][2] = bot.x; a[ts][3] = bot.y;
+            p1[ts] = pcur[pk[ts]];
+            p2[ts] = pcur[pkp[ts]];
+        }
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) {
+            const float s1 = p1[ts].x, tau1 = p1[ts].y, s2 = p2[ts].x, tau2 = p2[ts].y;
+            const float a00 = a[ts][0], a01 = a[ts][1], a10 = a[ts][2], a11 = a[ts][3];
+            // rows 2 k, 2 k + 1 : J^T from the left
+            const float b00 = a00 - s1 * (a10 + tau1 * a00), b01 = a01 - s1 * (a11 + tau1 * a01);
+            const float b10 = a10 + s1 * (a00 - tau1 * a10), b11 = a11 + s1 * (a01 - tau1 * a11);
+            // columns 2 k', 2 k' + 1 : J from the right
+            const float e00 = b00 - s2 * (b01 + tau2 * b00), e01 = b01 + s2 * (b00 - tau2 * b01);
+            const float e10 = b10 - s2 * (b11 + tau2 * b10), e11 = b11 + s2 * (b10 - tau2 * b11);
+            const float xa0 = hi16 ? e01 : e00, xb0 = hi16 ? e00 : e01;
+            const float xa1 = hi16 ? e11 : e10, xb1 = hi16 ? e10 : e11;
+            if (act[ts]) { nxt[wa[ts][0]] = xa0; nxt[wb[ts][0]] = xb0; nxt[wa[ts][1]] = xa1; nxt[wb[ts][1]] = xb1; }
+        }
+        __syncthreads();
+    };
+    // One sweep that starts in copy START1 (and ends in the other one: 127 is odd).
+    auto sweep_from = [&](auto start1, int t0) {
+        constexpr bool S1 = decltype(start1)::value;
+#pragma unroll 1
+        for (int round = 0; round < EIG_ROUNDS - 1; round += 2) {
+            round_step(EigBool<S1>{}, t0 + round);
+            round_step(EigBool<!S1>{}, t0 + round + 1);
+        }
+        round_step(EigBool<S1>{}, t0 + EIG_ROUNDS - 1);
+    };
+
     int sweeps_done = 0;
     for (int sweep = 0; sweep < EIG_MAX_SWEEPS; ++sweep) {
-        // off-diagonal norm
+        // off-diagonal norm (every index is at its own position between sweeps)
+        const float* cur = A2 + (sweeps_done & 1) * BUF;
         float off = 0.f;
         for (int idx = tid; idx < D * D; idx += EIG_THREADS) {
             int i = idx >> 7, j = idx & 127;
-            float v = A[idx];
-            if (i != j) off = fmaf(v, v, off);
+            float v = cur[i * EIG_LD + j];
+            if (i < j) off = fmaf(2.f * v, v, off);             // only the upper triangle is kept
         }
         off = wave_sum(off);
         if (lane == 0) red[16 + wave] = off;
@@ -536,86 +691,18 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
         for (int w = 0; w < 16; ++w) off2 += red[16 + w];
         __syncthreads();
         if (!(off2 > tol2)) break;      // uniform across the block
+        if (sweeps_done & 1) sweep_from(EigBool<true>{}, sweeps_done * EIG_ROUNDS);
+        else sweep_from(EigBool<false>{}, sweeps_done * EIG_ROUNDS);
         ++sweeps_done;
-
-        for (int round = 0; round < D - 1; ++round) {
-            if (tid < 64) {
-                int p, q;
-                rr_pair(round, tid, p, q);
-                // Rotations are applied as x' = x - s (y + tau x), y' = y + s (x - tau y) with
-                // tau = s / (1 + c): 1 - c is then carried to relative precision, so small
-                // angles (c rounding to 1) do not inflate the column norms of V.
-                float s, tau, t;
-                jacobi_params(A[p * D + p], A[q * D + q], A[p * D + q], thr_skip, s, tau, t);
-                rs[tid] = s;
-                rtau[tid] = tau;
-                rt[tid] = t;
-            }
-            __syncthreads();
-            int p2, q2;
-            rr_pair(round, lane, p2, q2);
-            const float s2 = rs[lane], tau2 = rtau[lane];
-            // A <- J^T A J : 64 x 64 blocks, wave handles pair-rows k = wave + 16 it;
-            // V <- V J     : 128 rows x 64 pairs.
-            // Software-pipelined by hand: the loads of block it + 1 are issued before the
-            // arithmetic and the stores of block it (every element belongs to exactly one thread
-            // per round, so the order is free; the compiler cannot know that and would keep each
-            // block's load -> math -> store chain serial, leaving the LDS idle while the VALU
-            // works and vice versa).
-            int pn, qn;
-            rr_pair(round, wave, pn, qn);
-            float n00 = A[pn * D + p2], n01 = A[pn * D + q2], n10 = A[qn * D + p2], n11 = A[qn * D + q2];
-            float ns1 = rs[wave], ntau1 = rtau[wave];
-            float nv0 = 0.f, nv1 = 0.f;
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int k = wave + 16 * it;
-                const int p = pn, q = qn;
-                const float a00 = n00, a01 = n01, a10 = n10, a11 = n11, s1 = ns1, tau1 = ntau1;
-                if (it < 3) {
-                    rr_pair(round, k + 16, pn, qn);
-                    n00 = A[pn * D + p2]; n01 = A[pn * D + q2];
-                    n10 = A[qn * D + p2]; n11 = A[qn * D + q2];
-                    ns1 = rs[k + 16]; ntau1 = rtau[k + 16];
-                } else {
-                    nv0 = V[wave * D + p2];
-                    nv1 = V[wave * D + q2];
-                }
-                // rows p, q : J^T from the left
-                float b00 = a00 - s1 * (a10 + tau1 * a00), b01 = a01 - s1 * (a11 + tau1 * a01);
-                float b10 = a10 + s1 * (a00 - tau1 * a10), b11 = a11 + s1 * (a01 - tau1 * a11);
-                // columns p', q' : J from the right
-                float e00 = b00 - s2 * (b01 + tau2 * b00), e01 = b01 + s2 * (b00 - tau2 * b01);
-                float e10 = b10 - s2 * (b11 + tau2 * b10), e11 = b11 + s2 * (b10 - tau2 * b11);
-                {                          // the pair's own block: annihilated exactly (branch-free)
-                    const bool own = k == lane;
-                    const float t = rt[k];
-                    e00 = own ? a00 - t * a01 : e00;
-                    e11 = own ? a11 + t * a01 : e11;
-                    e01 = own ? 0.f : e01;
-                    e10 = own ? 0.f : e10;
-                }
-                A[p * D + p2] = e00; A[p * D + q2] = e01;
-                A[q * D + p2] = e10; A[q * D + q2] = e11;
-            }
-#pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int i = wave + 16 * it;
-                const float v0 = nv0, v1 = nv1;
-                if (it < 7) {
-                    nv0 = V[(i + 16) * D + p2];
-                    nv1 = V[(i + 16) * D + q2];
-                }
-                V[i * D + p2] = v0 - s2 * (v1 + tau2 * v0);
-                V[i * D + q2] = v1 + s2 * (v0 - tau2 * v1);
-            }
-            __syncthreads();
-        }
     }
 
-    // ---- eigenvalues, rank, mask (integer logic), R, R_r, delta_mu -----------
-    if (tid == 0 && sweeps_out) sweeps_out[u] = sweeps_done;
-    if (tid < D) slam[tid] = A[tid * D + tid];
+    // ---- eigenvalues, rank, mask (integer logic) -----------------------------
+    const float* Af = A2 + (sweeps_done & 1) * BUF;
+    if (tid == 0) {
+        sweeps_ws[u] = sweeps_done;
+        if (sweeps_out) sweeps_out[u] = sweeps_done;
+    }
+    if (tid < D) slam[tid] = Af[tid * EIG_LD + tid];
     __syncthreads();
     if (tid < D) {
         float lc = slam[tid];
@@ -626,17 +713,84 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi(const float* __restric
         }
         lam_out[(size_t)u * D + tid] = lc;
         mask_out[(size_t)u * D + tid] = (uint8_t)(rank < r);
-        if (rank < r) { skeep[rank] = tid; keep_out[(size_t)u * r + rank] = tid; }
+        if (rank < r) keep_out[(size_t)u * r + rank] = tid;
     }
+}
+
+// V <- V J_1 J_2 ... over the recorded rounds, V = I at the start.  Wave = four rows of V; lane k
+// holds the elements at positions 2 k ("top") and 2 k + 1 ("bottom") of each row.  A round rotates
+// every lane's pair and then moves the columns to their next positions, which for this layout is a
+// shift of the tops by one lane upwards and of the bottoms by one lane downwards across the whole
+// wave (data-parallel-primitive moves, no LDS): lane 0 keeps its top, lane 1 takes lane 0's bottom
+// as its top, lane 63 takes its own top as its bottom.  Grid (8, U), 256 threads.
+__global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restrict__ rot,
+                                                           const int32_t* __restrict__ sweeps_ws,
+                                                           float* __restrict__ R_out)
+{
+    const int u = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row0 = (blockIdx.x * 4 + wave) * EIGV_ROWS;
+    const float2* rot_u = rot + (size_t)u * EIG_ROT_ROUNDS * 64 + lane;
+    const int n_rounds = min(max(sweeps_ws[u], 0), EIG_MAX_SWEEPS) * EIG_ROUNDS;
+    float top[EIGV_ROWS], bot[EIGV_ROWS];
+#pragma unroll
+    for (int i = 0; i < EIGV_ROWS; ++i) {
+        top[i] = (row0 + i == 2 * lane) ? 1.f : 0.f;
+        bot[i] = (row0 + i == 2 * lane + 1) ? 1.f : 0.f;
+    }
+    const bool lane1 = lane == 1;
+    auto apply = [&](float2 p) {
+#pragma unroll
+        for (int i = 0; i < EIGV_ROWS; ++i) {
+            const float x = top[i], y = bot[i];
+            const float xn = x - p.x * (y + p.y * x), yn = y + p.x * (x - p.y * y);
+            const float t_up = lane_from_below(xn, xn), b_up = lane_from_below(yn, yn);
+            top[i] = lane1 ? b_up : t_up;
+            bot[i] = lane_from_above(xn, yn);
+        }
+    };
+    constexpr int PF = 8;                                  // rounds of rotations requested ahead
+    float2 nx[PF];
+    int t = 0;
+    if (n_rounds >= PF) {
+#pragma unroll
+        for (int i = 0; i < PF; ++i) nx[i] = rot_u[(size_t)i * 64];
+        for (; t + 2 * PF <= n_rounds; t += PF) {
+#pragma unroll
+            for (int i = 0; i < PF; ++i) {
+                const float2 p = nx[i];
+                nx[i] = rot_u[(size_t)(t + PF + i) * 64];
+                apply(p);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PF; ++i) apply(nx[i]);
+        t += PF;
+    }
+    for (; t < n_rounds; ++t) apply(rot_u[(size_t)t * 64]);
+#pragma unroll
+    for (int i = 0; i < EIGV_ROWS; ++i)
+        *(float2*)(R_out + (size_t)u * D * D + (size_t)(row0 + i) * D + 2 * lane) = make_float2(top[i], bot[i]);
+}
+
+// R_r = R[:, keep] and delta_mu = mu - R_r R_r^T mu (Alg. 1 step 14 and 16), one work-group per matrix
+__global__ __launch_bounds__(256) void eig_finish(int r, const float* __restrict__ R, const int32_t* __restrict__ keep_idx,
+                                                  const float* __restrict__ mu_in, float* __restrict__ Rr_out,
+                                                  float* __restrict__ dmu_out)
+{
+    __shared__ int skeep[D];
+    __shared__ float sw[D];
+    const int u = blockIdx.x, tid = threadIdx.x;
+    const float* V = R + (size_t)u * D * D;
+    const float* mu = mu_in + (size_t)u * D;
+    if (tid < r) skeep[tid] = min(max(keep_idx[(size_t)u * r + tid], 0), D - 1);
     __syncthreads();
-    for (int idx = tid; idx < D * D; idx += EIG_THREADS) R_out[(size_t)u * D * D + idx] = V[idx];
-    for (int idx = tid; idx < D * r; idx += EIG_THREADS) {
+    for (int idx = tid; idx < D * r; idx += 256) {
         int c = idx / r, j = idx - c * r;
         Rr_out[(size_t)u * D * r + idx] = V[c * D + skeep[j]];
     }
-    const float* mu = mu_in + (size_t)u * D;
     if (tid < r) {
-        int col = skeep[tid];
+        const int col = skeep[tid];
         float w = 0.f;
         for (int c = 0; c < D; ++c) w = fmaf(V[c * D + col], mu[c], w);
         sw[tid] = w;
@@ -1022,12 +1176,19 @@ __global__ __launch_bounds__(128) void sigma_window_kernel(const T* __restrict__
 
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
-                      hipStream_t st)
+                      void* rotations, int32_t* sweeps_ws, hipStream_t st)
 {
-    hipError_t e = allow_dynamic_lds((const void*)eig_jacobi, EIG_LDS_BYTES);
+    hipError_t e = allow_dynamic_lds((const void*)eig_jacobi_rotations, EIG_LDS_BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(eig_jacobi, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, mu, r, R, lam,
-                       mask, keep_idx, Rr, dmu, sweeps);
+    hipLaunchKernelGGL(eig_jacobi_rotations, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, r, lam, mask,
+                       keep_idx, (float2*)rotations, sweeps_ws, sweeps);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(eig_apply_rotations, dim3(D / (4 * EIGV_ROWS), U), dim3(256), 0, st, (const float2*)rotations,
+                       sweeps_ws, R);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(eig_finish, dim3(U), dim3(256), 0, st, r, R, keep_idx, mu, Rr, dmu);
     return hipGetLastError();
 }
 

@@ -16,9 +16,12 @@ hipError_t launch_cov_partial(int dtype, bool mfma, const RowsDev& rows, int B, 
 hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks, bool center, bool tiled,
                                const float* part_S, const float* part_sum, float* cov, float* mu,
                                hipStream_t st);
+// rotations: eig_rotation_bytes(U) bytes of device scratch (the recorded Jacobi rotations),
+// sweeps_ws: U ints of device scratch; sweeps (optional) receives the sweep counts
+size_t eig_rotation_bytes(int U);
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
-                      hipStream_t st);
+                      void* rotations, int32_t* sweeps_ws, hipStream_t st);
 // Cholesky-based subspace iteration (Alg. 1 steps 6-13): V0 [U,d,k] -> Rr [U,d,k], dmu [U,d];
 // status [U] (optional): 0, or t+1 if iteration t met a non-positive pivot.
 int subspace_max_keep();
