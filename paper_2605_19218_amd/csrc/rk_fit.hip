@@ -493,7 +493,7 @@ __device__ __forceinline__ void jacobi_params(float app, float aqq, float apq, f
     }
 }
 
-constexpr int EIGV_ROWS = 4;
+// whole-wave lane shifts by one (data-parallel-primitive moves; the end lane has no source and keeps `keep`)
 __device__ __forceinline__ float lane_from_below(float keep, float v)      // lane i <- lane i - 1; lane 0 keeps `keep`
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, v),
@@ -723,6 +723,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
 // shift of the tops by one lane upwards and of the bottoms by one lane downwards across the whole
 // wave (data-parallel-primitive moves, no LDS): lane 0 keeps its top, lane 1 takes lane 0's bottom
 // as its top, lane 63 takes its own top as its bottom.  Grid (8, U), 256 threads.
+constexpr int EIGV_ROWS = 4;
 __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restrict__ rot,
                                                            const int32_t* __restrict__ sweeps_ws,
                                                            float* __restrict__ R_out)
@@ -773,34 +774,54 @@ __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restr
         *(float2*)(R_out + (size_t)u * D * D + (size_t)(row0 + i) * D + 2 * lane) = make_float2(top[i], bot[i]);
 }
 
-// R_r = R[:, keep] and delta_mu = mu - R_r R_r^T mu (Alg. 1 step 14 and 16), one work-group per matrix
+// R_r = R[:, keep] and delta_mu = mu - R_r R_r^T mu (Alg. 1 step 14 and 16), one work-group per matrix;
+// R is staged in LDS (row stride 129) so that the column reads below do not go to memory one by one.
+constexpr int EIGF_LD = D + 1;
+constexpr size_t EIGF_LDS_BYTES = (size_t)(D * EIGF_LD + 2 * D + 2 * D) * sizeof(float) + D * sizeof(int);
 __global__ __launch_bounds__(256) void eig_finish(int r, const float* __restrict__ R, const int32_t* __restrict__ keep_idx,
                                                   const float* __restrict__ mu_in, float* __restrict__ Rr_out,
                                                   float* __restrict__ dmu_out)
 {
-    __shared__ int skeep[D];
-    __shared__ float sw[D];
+    extern __shared__ float fsm[];
+    float* Vs = fsm;                          // [128][129]
+    float* part = Vs + D * EIGF_LD;           // [2][128] partial sums
+    float* sw = part + 2 * D;                 // [128] R_r^T mu
+    float* smu = sw + D;                      // [128]
+    int* skeep = (int*)(smu + D);             // [128]
     const int u = blockIdx.x, tid = threadIdx.x;
     const float* V = R + (size_t)u * D * D;
-    const float* mu = mu_in + (size_t)u * D;
+    for (int idx = tid; idx < D * D / 4; idx += 256) {
+        const float4 v = *(const float4*)(V + 4 * idx);
+        float* d = Vs + (idx >> 5) * EIGF_LD + 4 * (idx & 31);
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    }
+    if (tid < D) smu[tid] = mu_in[(size_t)u * D + tid];
     if (tid < r) skeep[tid] = min(max(keep_idx[(size_t)u * r + tid], 0), D - 1);
     __syncthreads();
     for (int idx = tid; idx < D * r; idx += 256) {
         int c = idx / r, j = idx - c * r;
-        Rr_out[(size_t)u * D * r + idx] = V[c * D + skeep[j]];
+        Rr_out[(size_t)u * D * r + idx] = Vs[c * EIGF_LD + skeep[j]];
     }
-    if (tid < r) {
-        const int col = skeep[tid];
+    const int half = tid >> 7, x = tid & (D - 1);
+    {                                          // w_j = sum_c V[c][keep_j] mu[c], rows split in two halves
         float w = 0.f;
-        for (int c = 0; c < D; ++c) w = fmaf(V[c * D + col], mu[c], w);
-        sw[tid] = w;
+        if (x < r) {
+            const int col = skeep[x];
+            for (int c = 64 * half; c < 64 * half + 64; ++c) w = fmaf(Vs[c * EIGF_LD + col], smu[c], w);
+        }
+        part[half * D + x] = w;
     }
     __syncthreads();
-    if (tid < D) {
+    if (tid < r) sw[tid] = part[tid] + part[D + tid];
+    __syncthreads();
+    {                                          // delta_mu[c] = mu[c] - sum_j V[c][keep_j] w_j, kept columns split in two halves
         float pr = 0.f;
-        for (int j = 0; j < r; ++j) pr = fmaf(V[tid * D + skeep[j]], sw[j], pr);
-        dmu_out[(size_t)u * D + tid] = mu[tid] - pr;
+        const int j0 = half ? (r + 1) / 2 : 0, j1 = half ? r : (r + 1) / 2;
+        for (int j = j0; j < j1; ++j) pr = fmaf(Vs[x * EIGF_LD + skeep[j]], sw[j], pr);
+        part[half * D + x] = pr;
     }
+    __syncthreads();
+    if (tid < D) dmu_out[(size_t)u * D + tid] = smu[tid] - (part[tid] + part[D + tid]);
 }
 
 __global__ __launch_bounds__(256) void gather_rotation_kernel(int r, const float* __restrict__ R,
@@ -1188,7 +1209,9 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
                        sweeps_ws, R);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(eig_finish, dim3(U), dim3(256), 0, st, r, R, keep_idx, mu, Rr, dmu);
+    e = allow_dynamic_lds((const void*)eig_finish, EIGF_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(eig_finish, dim3(U), dim3(256), EIGF_LDS_BYTES, st, r, R, keep_idx, mu, Rr, dmu);
     return hipGetLastError();
 }
 
