@@ -150,6 +150,46 @@ def test_eig_invariants_and_mask(ctx, with_sigma):
     assert torch.equal(Rr2, p.Rr)
 
 
+def test_eig_degenerate_inputs(ctx):
+    """Covariances the sweep loop must leave alone or handle without a rotation to find: all-zero Keys
+    (no sweep at all: R = I, every eigenvalue 0), Keys along the coordinate axes (a diagonal covariance:
+    R = I, the eigenvalues are the diagonal), a single token with centring (zero covariance), and Keys
+    that fill one 2-dimensional coordinate plane (one pair of the round-robin ordering carries everything)."""
+    B, Hkv, L, r = 4, 1, 64, 8
+    K = np.zeros((B, Hkv, L, D), dtype=np.float32)
+    for t in range(L):                                   # item 1: axis-aligned rows, channel 3 t mod 128
+        K[1, 0, t, (3 * t) % D] = 1.0 + (t % 5)
+    K[2, 0, 0] = np.linspace(-1.0, 1.0, D)               # item 2: only its first row counts (length 1)
+    ang = np.linspace(0.0, np.pi, L)
+    K[3, 0, :, 5] = np.cos(ang)                          # item 3: a plane spanned by channels 5 and 90
+    K[3, 0, :, 90] = 0.5 * np.sin(ang) + 0.25 * np.cos(ang)
+    lengths = [L, L, 1, L]
+    p = Pipeline(ctx, B, Hkv, Hkv, r, "f32", L)
+    Kd = to_dev(K, "f32")
+    n_dev = torch.tensor(lengths, device=DEV, dtype=torch.int32)
+    p.fit(Kd, L, n_dev=n_dev, center=False)
+    R, lam, sweeps, cov = to_host(p.R), to_host(p.lam), p.sweeps.cpu().numpy(), to_host(p.cov)
+    assert sweeps[0, 0] == 0 and np.array_equal(R[0, 0], np.eye(D)) and not lam[0, 0].any()
+    assert sweeps[1, 0] == 0 and np.array_equal(R[1, 0], np.eye(D))
+    assert np.array_equal(lam[1, 0], np.diag(cov[1, 0]).astype(np.float64))
+    # a rank-one covariance (one row, not centred) and the plane: invariants of a finished solve
+    for b in (2, 3):
+        assert 1 <= sweeps[b, 0] < 20
+        Rm, lm, C = R[b, 0], lam[b, 0], cov[b, 0]
+        assert np.abs(Rm.T @ Rm - np.eye(D)).max() <= 1e-5
+        assert np.linalg.norm(Rm.T @ C @ Rm - np.diag(lm)) <= 1e-5 * np.linalg.norm(C)
+        lam_o = np.linalg.eigvalsh(C)[::-1]
+        assert np.abs(np.sort(lm)[::-1] - lam_o).max() <= 1e-5 * lam_o[0]
+    assert (np.abs(lam[2, 0]) > 1e-6 * np.abs(lam[2, 0]).max()).sum() == 1
+    assert (np.abs(lam[3, 0]) > 1e-6 * np.abs(lam[3, 0]).max()).sum() == 2
+    # centring a single token leaves only the rounding of the fp32 products: a finished solve of noise
+    p.fit(Kd, L, n_dev=n_dev, center=True)
+    assert p.sweeps.cpu().numpy()[2, 0] < 20
+    assert np.abs(to_host(p.lam)[2, 0]).max() <= 1e-6 * float((K[2, 0, 0].astype(np.float64) ** 2).sum())
+    Rm = to_host(p.R)[2, 0]
+    assert np.abs(Rm.T @ Rm - np.eye(D)).max() <= 1e-5
+
+
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,r,generic,L,lengths", [
     ("f32", 32, False, 333, [333, 70]), ("bf16", 64, False, 333, [333, 70]), ("bf16", 64, True, 333, [333, 70]),
