@@ -57,6 +57,9 @@ typedef enum {
 
 enum { RK_F32 = 0, RK_BF16 = 1 };
 
+/* Largest token count per sequence that any size field may hold (capacity, max_seq_len, n_tokens). */
+#define RK_MAX_TOKENS (1 << 30)
+
 /* rk_fit_rotation flags */
 enum {
     RK_FIT_CENTER = 1u        /* subtract the per-head channel mean (Alg. 1 steps 1-2).
@@ -84,7 +87,7 @@ typedef struct {
     int32_t head_dim;         /* d = 128                                              */
     int32_t keep;             /* r: kept channels per head, 1..d                      */
     int32_t dtype;            /* RK_F32 | RK_BF16                                     */
-    int32_t capacity;         /* tokens allocated per (b, h_kv) in K~ and V; multiple of 32 */
+    int32_t capacity;         /* tokens allocated per (b, h_kv) in K~ and V; multiple of 32, <= RK_MAX_TOKENS */
     int32_t max_seq_len;      /* host upper bound on seq_len[b]                       */
     const int32_t* seq_len;   /* device [B]: tokens currently cached per sequence     */
 } rk_layout;

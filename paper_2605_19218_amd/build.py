@@ -67,5 +67,29 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(outdir: str) -> str:
+    """A second copy of the library, in `outdir`, whose HOST code is built with AddressSanitizer and
+    UndefinedBehaviorSanitizer (the device code is compiled unoptimised: it is never run).  For host-only
+    runs on a context without a device; the GPU sanitizers are not used."""
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    common = [hipcc(), "--offload-arch=gfx950", "-O1", "-Xarch_device", "-O0", "-g", "-std=c++17", "-fPIC",
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC] + san
+    objs = [os.path.join(outdir, s.replace(".hip", ".o")) for s in SOURCES]
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+        jobs = [ex.submit(_run, common + ["-c", os.path.join(CSRC, s), "-o", o], False) for s, o in zip(SOURCES, objs)]
+        for j in jobs:
+            j.result()
+    lib = os.path.join(outdir, "librotatek_san.so")
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + san[:4] + ["-o", lib] + objs, False)
+    return lib
+
+
+def host_clang() -> str:
+    """The C compiler that matches the sanitizer run-time of build_host_sanitized (ROCm's clang)."""
+    return os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(hipcc()))), "lib", "llvm", "bin", "clang")
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

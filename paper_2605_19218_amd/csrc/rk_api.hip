@@ -68,6 +68,9 @@ rk_status check_layout(rk_ctx* ctx, const rk_layout* L)
     if (L->capacity < 32 || L->capacity % 32 != 0)
         return fail(ctx, RK_ERR_INVALID_ARG, "capacity %d must be a positive multiple of 32", L->capacity);
     if (L->max_seq_len < 0) return fail(ctx, RK_ERR_INVALID_ARG, "max_seq_len is negative");
+    // token counts stay below 2^30, so that rounding one up to a tile never leaves the range of int
+    if (L->capacity > RK_MAX_TOKENS || L->max_seq_len > RK_MAX_TOKENS)
+        return fail(ctx, RK_ERR_INVALID_ARG, "capacity / max_seq_len exceed %d tokens", RK_MAX_TOKENS);
     return RK_OK;
 }
 
@@ -75,6 +78,7 @@ rk_status check_rows(rk_ctx* ctx, const rk_layout* L, const rk_rows* r, const ch
 {
     if (!r || !r->data) return fail(ctx, RK_ERR_INVALID_ARG, "%s: NULL", name);
     if (r->n_tokens < 0) return fail(ctx, RK_ERR_INVALID_ARG, "%s: n_tokens is negative", name);
+    if (r->n_tokens > RK_MAX_TOKENS) return fail(ctx, RK_ERR_INVALID_ARG, "%s: n_tokens exceeds %d", name, RK_MAX_TOKENS);
     if (r->tok_idx && !r->tok_off) return fail(ctx, RK_ERR_INVALID_ARG, "%s: tok_idx given without tok_off", name);
     if (r->stride_t < D || r->stride_b < 0 || r->stride_h < 0)
         return fail(ctx, RK_ERR_INVALID_ARG, "%s: bad strides", name);
@@ -103,7 +107,7 @@ FitWs fit_ws(const rk_layout* L, int max_tokens)
     FitWs w;
     w.part_S = 0;
     size_t first = U * nc * D * D * sizeof(float);
-    if (first < eig_rotation_bytes((int)U)) first = eig_rotation_bytes((int)U);
+    if (first < eig_rotation_bytes(U)) first = eig_rotation_bytes(U);
     w.part_sum = align_up(w.part_S + first, 256);
     w.cov = align_up(w.part_sum + U * nc * D * sizeof(float), 256);
     w.sweeps = align_up(w.cov + U * D * D * sizeof(float), 256);
@@ -273,7 +277,7 @@ rk_status rk_validate_layout(const rk_layout* L) { return check_layout(nullptr, 
 
 size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens)
 {
-    if (check_layout(nullptr, L) != RK_OK || max_tokens < 0) return 0;
+    if (check_layout(nullptr, L) != RK_OK || max_tokens < 0 || max_tokens > RK_MAX_TOKENS) return 0;
     return fit_ws(L, max_tokens).total;
 }
 

@@ -458,7 +458,7 @@ __device__ __forceinline__ constexpr int eig_upper(int r, int c)
     return ((r >> 1) < (c >> 1) || ((r >> 1) == (c >> 1) && r <= c)) ? r * (D + 2) + c : c * (D + 2) + r;
 }
 
-size_t eig_rotation_bytes(int U) { return (size_t)U * EIG_ROT_ROUNDS * 64 * sizeof(float2); }
+size_t eig_rotation_bytes(size_t U) { return U * EIG_ROT_ROUNDS * 64 * sizeof(float2); }
 
 // position of a row / column after one round
 __host__ __device__ constexpr int eig_next_pos(int p)

@@ -18,7 +18,7 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
                                hipStream_t st);
 // rotations: eig_rotation_bytes(U) bytes of device scratch (the recorded Jacobi rotations),
 // sweeps_ws: U ints of device scratch; sweeps (optional) receives the sweep counts
-size_t eig_rotation_bytes(int U);
+size_t eig_rotation_bytes(size_t U);
 hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* mu, int r, float* R,
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       void* rotations, int32_t* sweeps_ws, hipStream_t st);
