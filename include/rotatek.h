@@ -11,7 +11,10 @@
  * Conventions
  *   - Every tensor argument is a DEVICE pointer owned by the caller.  The
  *     library never allocates, frees or retains tensor memory; scratch comes
- *     from a caller-provided workspace sized by rk_*_workspace_size().
+ *     from a caller-provided workspace sized by rk_*_workspace_size().  The
+ *     only device memory of its own is what a context holds from rk_create to
+ *     rk_destroy (512 KB of counters) and the fixed scratch array behind
+ *     rk_decode_attn_static; no other call allocates or frees.
  *   - All kernels are enqueued on the caller's stream (`stream` is a
  *     hipStream_t passed as void*; NULL = the default stream).  Calls are
  *     asynchronous.  Argument validation is synchronous and precedes any launch.
@@ -135,7 +138,8 @@ typedef struct {
     float* mu;           /* [B,H_kv,d]    per-head channel mean of the fitted Keys             */
     float* delta_mu;     /* [B,H_kv,d]    mu - R_r R_r^T mu  (Alg. 1 step 15)                   */
     float* cov;          /* optional [B,H_kv,d,d]: the un-weighted scatter of Alg. 1 step 3     */
-    int32_t* sweeps;     /* optional [B,H_kv] (int32): Jacobi sweeps the eigensolver used        */
+    int32_t* sweeps;     /* optional [B,H_kv] (int32): Jacobi sweeps the eigensolver used; 20 (its limit)
+                          * means that the off-diagonal norm was still above 2e-8 ||C_q||_F: not converged */
 } rk_fit_out;
 
 /* ---- context ------------------------------------------------------------- */
@@ -180,6 +184,8 @@ rk_status rk_stream_read(rk_ctx* ctx, const void* src, size_t bytes, void* strea
  * C_q ("Query-Weighted PCA": R = eigenvectors of C_q); rank of every
  * eigenvalue (descending, ties -> lower column) -> mask, keep_idx, R_r;
  * delta_mu (step 15).  n_b = 0 gives mu = 0, C = 0 (R = I).
+ * The eigensolver is a parallel Jacobi iteration that stops when the off-diagonal
+ * Frobenius norm is at most 2e-8 ||C_q||_F, or after 20 sweeps (see `sweeps`).
  * Errors: INVALID_ARG (NULL required pointer, bad strides/sizes), UNSUPPORTED,
  * WORKSPACE, HIP.                                                             */
 rk_status rk_fit_rotation(rk_ctx* ctx, const rk_layout* L, const rk_rows* keys,
