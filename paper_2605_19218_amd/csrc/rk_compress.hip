@@ -94,17 +94,29 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
     const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
     bf16_t* Ku = Kp + (size_t)u * cap * R;
 
-    // Key rows of one pass of this wave, straight into B-operand registers.  Every row is read
-    // once: non-temporal.  Rows past the end are clamped to the last row (never stored).
-    auto load_keys = [&](bf16x8 (&kb)[Cfg::TT][4], int w0) {
+    // Row numbers of one pass of this wave (token list entries; the token itself without a list).
+    // Rows past the end are clamped to the last row (never stored).
+    auto load_rows_idx = [&](int (&idx)[Cfg::TT], int w0) {
 #pragma unroll
         for (int tt = 0; tt < Cfg::TT; ++tt) {
             const int tok = min(w0 + tt * 16 + n, n_b - 1);
-            const bf16_t* row = base + row_off<GATHER>(hb, rows.st, list, tok);
+            idx[tt] = GATHER ? list[tok] : tok;
+        }
+    };
+    // Key rows of one pass, straight into B-operand registers.  Every row is read once: non-temporal.
+    auto load_keys_at = [&](bf16x8 (&kb)[Cfg::TT][4], const int (&idx)[Cfg::TT]) {
+#pragma unroll
+        for (int tt = 0; tt < Cfg::TT; ++tt) {
+            const bf16_t* row = base + hb + (int64_t)idx[tt] * rows.st;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 kb[tt][i] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)(row + 32 * i + 8 * g)));
         }
+    };
+    auto load_keys = [&](bf16x8 (&kb)[Cfg::TT][4], int w0) {
+        int idx[Cfg::TT];
+        load_rows_idx(idx, w0);
+        load_keys_at(kb, idx);
     };
     // rotate one pass and store its packed rows
     auto rotate_store = [&](const bf16x8 (&kb)[Cfg::TT][4], int w0, auto all_valid) {
@@ -202,20 +214,52 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
         static_assert(Cfg::PASSES % 2 == 0 && Cfg::PASSES >= 4, "passes are taken in pairs");
         constexpr int TP = Cfg::TOK_PER_PASS;
         bf16x8 ka[Cfg::TT][4], kc[Cfg::TT][4];
-        load_keys(ka, w_first);
+        if (!GATHER) {
+            load_keys(ka, w_first);
+            __builtin_amdgcn_sched_barrier(0);
+            park_fragments();
+            __syncthreads();
+#pragma unroll 1
+            for (int p = 0; p < Cfg::PASSES - 2; p += 2) {
+                load_keys(kc, w_first + (p + 1) * TP);
+                __builtin_amdgcn_sched_barrier(0);
+                rotate_store(ka, w_first + p * TP, std::true_type{});
+                load_keys(ka, w_first + (p + 2) * TP);
+                __builtin_amdgcn_sched_barrier(0);
+                rotate_store(kc, w_first + (p + 1) * TP, std::true_type{});
+            }
+            load_keys(kc, w_first + (Cfg::PASSES - 1) * TP);
+            __builtin_amdgcn_sched_barrier(0);
+            rotate_store(ka, w_first + (Cfg::PASSES - 2) * TP, std::true_type{});
+            rotate_store(kc, w_first + (Cfg::PASSES - 1) * TP, std::true_type{});
+            return;
+        }
+        // With a token list a row's address comes from a load.  The row numbers of pass p + 2 are
+        // requested BEFORE the rows of pass p + 1, so that waiting for them (the oldest loads in flight
+        // by then) leaves the rows of the pass in between in flight; requested together with the rows
+        // they address, every pass would begin with a full round trip and an empty pipeline.
+        int ia[Cfg::TT], ic[Cfg::TT];
+        load_rows_idx(ia, w_first);
+        load_rows_idx(ic, w_first + TP);
+        __builtin_amdgcn_sched_barrier(0);
+        load_keys_at(ka, ia);
         __builtin_amdgcn_sched_barrier(0);
         park_fragments();
         __syncthreads();
 #pragma unroll 1
         for (int p = 0; p < Cfg::PASSES - 2; p += 2) {
-            load_keys(kc, w_first + (p + 1) * TP);
+            load_rows_idx(ia, w_first + (p + 2) * TP);
+            __builtin_amdgcn_sched_barrier(0);
+            load_keys_at(kc, ic);
             __builtin_amdgcn_sched_barrier(0);
             rotate_store(ka, w_first + p * TP, std::true_type{});
-            load_keys(ka, w_first + (p + 2) * TP);
+            load_rows_idx(ic, w_first + min(p + 3, Cfg::PASSES - 1) * TP);
+            __builtin_amdgcn_sched_barrier(0);
+            load_keys_at(ka, ia);
             __builtin_amdgcn_sched_barrier(0);
             rotate_store(kc, w_first + (p + 1) * TP, std::true_type{});
         }
-        load_keys(kc, w_first + (Cfg::PASSES - 1) * TP);
+        load_keys_at(kc, ic);
         __builtin_amdgcn_sched_barrier(0);
         rotate_store(ka, w_first + (Cfg::PASSES - 2) * TP, std::true_type{});
         rotate_store(kc, w_first + (Cfg::PASSES - 1) * TP, std::true_type{});

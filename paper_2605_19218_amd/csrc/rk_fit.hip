@@ -128,6 +128,21 @@ __device__ __forceinline__ void covm_load_full(uint4 (&r)[8], const bf16_t* __re
     }
 }
 
+// Token-list form: the row numbers of a k-step (eight per lane) and the rows they address are
+// two loads in a chain.  The row numbers are requested a whole turn of the stage ring ahead of
+// their rows, so that the wait for them does not drain the rows in flight.
+__device__ __forceinline__ void covm_load_idx(int (&ix)[8], const int32_t* __restrict__ list, int tok0, int t_last)
+{
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) ix[jj] = list[min(tok0 + jj, t_last)];
+}
+__device__ __forceinline__ void covm_load_rows(uint4 (&r)[8], const bf16_t* __restrict__ base, int64_t head_base,
+                                               int64_t st, const int (&ix)[8], int o)
+{
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) r[jj] = *(const uint4*)(base + head_base + (int64_t)ix[jj] * st + 8 * o);
+}
+
 template <bool GATHER>
 __device__ __forceinline__ void covm_load(uint4 (&r)[8], const bf16_t* __restrict__ base, int64_t head_base,
                                           int64_t st, const int32_t* __restrict__ list, int tok0, int t_end,
@@ -256,7 +271,27 @@ __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, i
         constexpr int NKW = COVM_TOK_PER_WAVE / 16;
         const int shift = (nfull == NKW) ? ((wave * 8 + chunk * 5 + u * 11) & (NKW - 1)) : 0;
 #define KSTEP_TOK(i) (16 * (((i) + shift) & (NKW - 1)))
-        if (nfull >= 2 * COVM_STAGES) {
+        if (GATHER && nfull >= 2 * COVM_STAGES) {
+            int ix[COVM_STAGES][8];
+#pragma unroll
+            for (int s = 0; s < COVM_STAGES; ++s) covm_load_idx(ix[s], list, tw0 + KSTEP_TOK(s) + 8 * g2, tw1 - 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < COVM_STAGES; ++s) {
+                covm_load_rows(st[s], base, hb, rst, ix[s], o);
+                covm_load_idx(ix[s], list, tw0 + KSTEP_TOK(s + COVM_STAGES) + 8 * g2, tw1 - 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            for (; ks + 2 * COVM_STAGES <= nfull; ks += COVM_STAGES) {
+#pragma unroll
+                for (int s = 0; s < COVM_STAGES; ++s) {
+                    covm_step(st[s], sel, acc, csum);
+                    covm_load_rows(st[s], base, hb, rst, ix[s], o);           // k-step ks + s + STAGES
+                    covm_load_idx(ix[s], list, tw0 + KSTEP_TOK(ks + s + 2 * COVM_STAGES) + 8 * g2, tw1 - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else if (nfull >= 2 * COVM_STAGES) {
             // Long chunk (the normal case).  The fill and the steady loop use plain loads of
             // full k-steps with no branch anywhere near them, so every wait on them is exact
             // (a conservative wait-count state entering the loop would be paid every iteration).
