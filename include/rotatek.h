@@ -158,7 +158,10 @@ rk_status rk_validate_layout(const rk_layout* L);
 /* Bytes the caller must allocate for the packed-Key cache and the Value cache. */
 rk_status rk_cache_bytes(const rk_layout* L, size_t* k_packed_bytes, size_t* v_cache_bytes);
 
-/* Bytes of workspace rk_fit_rotation needs for at most max_tokens rows per sequence. */
+/* Bytes of workspace rk_fit_rotation / rk_fit_subspace need for at most max_tokens rows per sequence
+ * (0 for an invalid layout or max_tokens outside 0..RK_MAX_TOKENS).  At least 1.3 MB per (b, h_kv):
+ * the eigensolver records its rotations there (up to 20 sweeps) after the covariance partials,
+ * 64 KB per 2048 rows, are no longer needed. */
 size_t rk_fit_workspace_size(const rk_layout* L, int32_t max_tokens);
 /* Bytes of workspace rk_decode_attn needs (depends on batch, heads, max_seq_len). */
 size_t rk_decode_workspace_size(const rk_ctx* ctx, const rk_layout* L);
