@@ -298,13 +298,16 @@ rk_status rk_decode_attn_static(rk_ctx* ctx, const rk_layout* L, const void* q, 
  * k_new R_r / v_new, the softmax runs over seq_len[b] + 1 tokens (the new one
  * included), and seq_len[b] += 1 on the device.  Results equal rk_append then
  * rk_decode_attn up to fp32 rounding order (the stored row may differ from
- * rk_append's by one unit in the last place of the storage type).  On the
- * matrix-core path with H_q/H_kv < 16 the append rides in the
- * decode's two launches (k_new takes a free column of the q~ = q R_r product);
- * otherwise the call issues rk_append's and rk_decode_attn's launches.
+ * rk_append's by one unit in the last place of the storage type plus the fp32
+ * accumulation bound).  On the matrix-core path with H_q/H_kv < 16 the append
+ * rides in the decode's own launches (k_new takes a free column of the
+ * q~ = q R_r product): one launch where rk_decode_attn is one launch, else the
+ * split and the merge launch; otherwise the call issues rk_append's and
+ * rk_decode_attn's launches.  Calls on one context that overlap in time (two
+ * streams) share the context's counters and must not be made.
  * L->max_seq_len bounds seq_len[b] BEFORE the call; L->seq_len is ignored in
  * favour of `seq_len` (device [B], read and written).  k_new, v_new: [B,H_kv,d],
- * q, out: [B,H_q,d], all L->dtype; q and k_new 16-byte aligned.  Workspace:
+ * q, out: [B,H_q,d], all L->dtype; q, k_new and v_new 16-byte aligned.  Workspace:
  * rk_decode_workspace_size of the layout with max_seq_len + 1.  A sequence
  * already at capacity is left untouched and attends over what it has.
  * Errors: INVALID_ARG, CAPACITY (max_seq_len + 1 > capacity; nothing is

@@ -579,7 +579,7 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
                       L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, nullptr,
                       tk_new ? &ta : nullptr, sc, out, (float*)workspace,
                       ctx->fuse_merge && ctx->xcd_deal_ok ? ctx->tickets + APP_TICKETS : nullptr, DEC_COUNTERS,
-                      as_stream(stream));
+                      nullptr, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }
@@ -632,8 +632,9 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
     if (s != RK_OK) return s;
     if (!k_new || !v_new || !q || !R_r || !k_packed || !v_cache || !seq_len || !out)
         return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: NULL pointer");
-    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)k_new & 15) || ((uintptr_t)q & 15))
-        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: q, k_new and the caches must be 16-byte aligned");
+    if (((uintptr_t)k_packed & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)k_new & 15) || ((uintptr_t)v_new & 15) ||
+        ((uintptr_t)q & 15))
+        return fail(ctx, RK_ERR_INVALID_ARG, "append_decode: q, k_new, v_new and the caches must be 16-byte aligned");
     if (L->max_seq_len + 1 > L->capacity)
         return fail(ctx, RK_ERR_CAPACITY, "append_decode: %d + 1 rows exceed capacity %d", L->max_seq_len,
                     L->capacity);
@@ -666,7 +667,8 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
     }
     e = launch_decode(L->dtype, mfma, L->batch, L->n_q_heads, L->n_kv_heads, L->capacity, L->keep, S, tiles, q,
                       k_packed, v_cache, R_r, delta_mu, seq_len, nullptr, fused ? &app : nullptr, nullptr, sc, out,
-                      (float*)workspace, nullptr, 0, st);
+                      (float*)workspace, ctx->fuse_merge && ctx->xcd_deal_ok ? ctx->tickets + APP_TICKETS : nullptr,
+                      DEC_COUNTERS, ctx->tickets, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }

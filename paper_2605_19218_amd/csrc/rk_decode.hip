@@ -746,8 +746,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const float* __restrict__ dmu, const int32_t* seq_len, int Hq, int Hkv, int cap, int r, int tiles_all,
     float scale_log2, float* ws_m, float* ws_l, float* ws_acc, int S,
     bf16_t* __restrict__ out, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
-    float* __restrict__ ws_snew, TextAppendDev ta, TextDev text, int TS, int SP, int n_vis,
-    bf16_t* __restrict__ out_merged, int32_t* done)
+    float* ws_snew, TextAppendDev ta, TextDev text, int TS, int SP, int n_vis,
+    bf16_t* __restrict__ out_merged, int32_t* done, int32_t* batch_tickets, int32_t* seq_len_rw)
 {
     typedef DecTile<R> Tile;
     constexpr int NF = Tile::NF, NFA = Tile::NFA;
@@ -1124,8 +1124,19 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         // mapping above), so the one that draws the last ticket finds all S partials in that same L2.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (tid == 0)
+        if (tid == 0) {
             sm_last = __hip_atomic_fetch_add(done + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == S - 1;
+            if (STEP && app) {
+                // Fused append: the length of sequence b moves once every work-group of the batch item
+                // (all units, all splits: they sit on different XCDs, hence a device-wide counter) has
+                // read the old one and is done with it; whoever draws the item's last ticket does it.
+                const int all = Hkv * ngrp * S;
+                if (__hip_atomic_fetch_add(batch_tickets + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == all - 1) {
+                    batch_tickets[b] = 0;
+                    if (app_ok) seq_len_rw[b] = seq_raw + 1;
+                }
+            }
+        }
         __syncthreads();
         if (!sm_last) return;
         const int hh = tid >> 4, c0 = (tid & 15) * 8;           // thread = (head, 8 channels)
@@ -1136,8 +1147,28 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
             const float* pa = ws_acc + row * SP * D + c0;
             float M = NEG_INF, den = 0.f;
             f32x4 n0 = (f32x4){0.f, 0.f, 0.f, 0.f}, n1 = n0;
+            float sx = NEG_INF;
+            uint4 vraw = make_uint4(0, 0, 0, 0);
+            if (STEP && app) {                                   // the appended token: one more term of the softmax
+                sx = ws_snew[row];
+                vraw = *(const uint4*)(v_new + (size_t)u * D + c0);
+            }
             if (S <= 8) fold_partials<8>(pm, pl, pa, S, M, den, n0, n1);     // one round trip to the L2
             else fold_partials<16>(pm, pl, pa, S, M, den, n0, n1);
+            if (STEP && sx > NEG_INF) {
+                const float Mc = fmaxf(M, sx);
+                const float resc = exp2f(M - Mc), w = exp2f(sx - Mc);
+                const uint32_t vw[4] = {vraw.x, vraw.y, vraw.z, vraw.w};
+                den = fmaf(den, resc, w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = bf16_to_f32((bf16_t)(vw[e >> 1] >> (16 * (e & 1))));
+                    const float hi = bf16_to_f32((bf16_t)(vw[2 + (e >> 1)] >> (16 * (e & 1))));
+                    n0[e] = fmaf(n0[e], resc, lo * w);
+                    n1[e] = fmaf(n1[e], resc, hi * w);
+                }
+                M = Mc;
+            }
             const float inv = (M > NEG_INF) ? 1.f / den : 0.f;
             uint4 pk;
             pk.x = (uint32_t)f32_to_bf16(n0[0] * inv) | ((uint32_t)f32_to_bf16(n0[1] * inv) << 16);
@@ -1159,24 +1190,29 @@ static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf1
                                  const float* Rr, const float* dmu, const int32_t* seq_len, int Hq, int Hkv, int cap,
                                  int r, int tiles_all, float sl2, float* m, float* l, float* acc, int S, bf16_t* out,
                                  const bf16_t* k_new, const bf16_t* v_new, float* snew, const TextAppendDev& ta,
-                                 const TextDev& text, int TS, int SP, int n_vis, bf16_t* out_merged, int32_t* done)
+                                 const TextDev& text, int TS, int SP, int n_vis, bf16_t* out_merged, int32_t* done,
+                                 int32_t* batch_tickets, int32_t* seq_len_rw)
 {
-    if (out_merged)
+    if (out_merged && k_new)
+        hipLaunchKernelGGL((decode_split_mfma<R, true, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
+    else if (out_merged)
         hipLaunchKernelGGL((decode_split_mfma<R, false, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis, out_merged, done);
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
     else if (TS > 0)
         hipLaunchKernelGGL((decode_split_mfma<R, false, true, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis, out_merged, done);
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
     else if (k_new || ta.k)
         hipLaunchKernelGGL((decode_split_mfma<R, true, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis, out_merged, done);
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
     else
         hipLaunchKernelGGL((decode_split_mfma<R, false, false, false>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
-                           SP, n_vis, out_merged, done);
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
 }
 
 // The fused append needs a free MFMA column next to the query heads: one group of fewer than 16.
@@ -1197,7 +1233,8 @@ int decode_text_slices(int dtype, bool mfma, int r, const TextDev* text)
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
-                         float scale, void* out, float* ws, int32_t* counters, int n_counters, hipStream_t st)
+                         float scale, void* out, float* ws, int32_t* counters, int n_counters, int32_t* batch_tickets,
+                         hipStream_t st)
 {
     const size_t rows = (size_t)B * Hq;
     const int TS = decode_text_slices(dtype, mfma, r, text);
@@ -1222,7 +1259,7 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         // Merge folded into the split launch: a plain decode with several splits whose units deal
         // out evenly over the 8 XCDs (the splits of a unit share an XCD there; an uneven deal would
         // leave XCDs idle, which costs more than the second launch saves)
-        const bool fused_merge = !text && !app && S >= 2 && counters && nunit <= n_counters &&
+        const bool fused_merge = !text && (!app || batch_tickets) && S >= 2 && counters && nunit <= n_counters &&
                                  (nunit % 8 == 0 || nunit >= 160);
         if (fused_merge) {
             grid = dim3((unsigned)(8 * ((nunit + 7) / 8) * S));
@@ -1238,7 +1275,8 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
     case RV:                                                                                               \
         launch_decode_mfma_r<RV>(grid, st, q_, k_, v_, Rr, dmu, seq_len, Hq, Hkv, cap, r, tiles_all, sl2, ws_m,   \
                                  ws_l, ws_acc, S, direct ? (bf16_t*)out : nullptr, kn, vn, ws_snew, ta, tx, TS, SP, \
-                                 n_vis, fused_merge ? (bf16_t*)out : nullptr, counters);                   \
+                                 n_vis, fused_merge ? (bf16_t*)out : nullptr, counters, batch_tickets,     \
+                                 app ? app->seq_len : nullptr);                                            \
         break;
         switch (keep_padded(r)) {
             RK_CASE(16) RK_CASE(32) RK_CASE(48) RK_CASE(64) RK_CASE(80) RK_CASE(96) RK_CASE(112) RK_CASE(128)

@@ -87,10 +87,13 @@ bool decode_append_fusable(int dtype, bool mfma, int Hq, int Hkv, int r);
 //           fold its partials inside the split launch (one counter per (b, h_kv, head group)).  Only
 //           valid on a device that deals work-groups to its XCDs round-robin by linear index
 //           (probe_xcd_deal)
+// batch_tickets: B ints that are zero between launches (or null): with them a fused append is folded
+//           the same way and the launch bumps seq_len itself
 hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, int r, int S, int tiles_all,
                          const void* q, const void* Kp, const void* Vc, const float* Rr, const float* dmu,
                          const int32_t* seq_len, const TextDev* text, const AppendDev* app, const TextAppendDev* tapp,
-                         float scale, void* out, float* ws, int32_t* counters, int n_counters, hipStream_t st);
+                         float scale, void* out, float* ws, int32_t* counters, int n_counters, int32_t* batch_tickets,
+                         hipStream_t st);
 // Whether work-groups whose linear indices agree modulo 8 run on the same XCD (true on MI355X in every
 // partition mode).  Launches a tiny kernel that records each work-group's XCD and synchronises;
 // scratch: 64 ints of device memory, left zeroed.

@@ -109,6 +109,41 @@ def test_fused_full_size_gqa_16k(ctx):
         check_out(got, oracle_decode(p, new["q"], [L + step + 1] * B), dtype)
 
 
+@pytest.mark.parametrize("shape", [(2, 28, 4, 2500, [2500, 1100], 64), (8, 8, 8, 1200, [1200, 0, 5, 700, 1200, 64, 333, 1], 48),
+                                   (4, 12, 6, 4096, [4096, 4096, 2048, 4000], 96)])
+def test_fused_append_folded_against_two_launches(ctx, shape):
+    """The fused append with the split-K merge folded into its launch (the length bumped by the last
+    work-group of a batch item) against the same steps with the separate merge launch: same lengths,
+    bit-equal stored rows, outputs within the output tolerance of each other and of the oracle, and
+    bit-equal outputs when the folded form is repeated from the same state.  The unit counts (8, 64, 24
+    head groups) all deal evenly over the 8 XCDs, and every shape plans at least two splits."""
+    B, Hq, Hkv, L, lengths, r = shape
+    dtype = "bf16"
+    data = layer(B, Hq, Hkv, L, dtype, 64, lengths=lengths)
+    a = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, lengths=lengths, cap=L + 4)
+    a.max_seq_len = max(lengths)
+    n_splits, _ = rk.rk_decode_plan(ctx, a.layout())
+    assert n_splits >= 2
+    two, again = clone_state(ctx, a), clone_state(ctx, a)
+    lens = list(lengths)
+    for step in range(3):
+        new = layer(B, Hq, Hkv, 1, dtype, 6400 + step)
+        kn, vn, q = to_dev(new["k_new"], dtype), to_dev(new["v_new"], dtype), to_dev(new["q"], dtype)
+        got = a.append_decode(kn, vn, q).copy()
+        rep = again.append_decode(kn, vn, q).copy()
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 0)
+        try:
+            ref = two.append_decode(kn, vn, q).copy()
+        finally:
+            rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 1)
+        lens = [x + 1 for x in lens]
+        assert a.seq_len.cpu().tolist() == lens and two.seq_len.cpu().tolist() == lens
+        assert np.array_equal(got, rep)
+        check_out(got, ref, dtype)
+        check_out(got, oracle_decode(a, new["q"], lens), dtype)
+        assert torch.equal(a.Kp, two.Kp) and torch.equal(a.Vc, two.Vc)
+
+
 def test_fused_new_token_matters(ctx):
     """Vacuity guard: a new Key aligned with the query must change the output visibly,
     i.e. the appended row really takes part in the softmax of its own step."""
