@@ -763,9 +763,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const bool direct = out != nullptr;     // the only split of a single-path call writes the result itself
     // Fused frozen-R append (k_new != NULL; the host guarantees G < 16 and never combines it
     // with `direct`): k_new rides through the q~ MFMAs as column 15, which the query heads
-    // leave free, so k~_new = k_new R_r costs nothing.  Split 0 stores the new row
-    // (position seq_len[b], which no split of this launch scores: the length is bumped by the
-    // merge kernel) and hands the row's own score to the merge kernel.
+    // leave free, so k~_new = k_new R_r costs nothing.  Split 0 stores the new row (position
+    // seq_len[b], which no split of this launch scores) and hands the row's own score to whoever
+    // folds the partials: the merge kernel, which then also bumps the length, or with FUSED the
+    // unit's last work-group (the length is bumped by the batch item's last work-group, see below).
     const bool app = STEP && k_new != nullptr;
     const int G = Hq / Hkv;
     const int ngrp = (G + 15) >> 4;

@@ -58,7 +58,8 @@ struct TextDev {
 struct AppendDev {
     const void* k_new;       // [B, H_kv, d]
     const void* v_new;       // [B, H_kv, d]
-    int32_t* seq_len;        // the same array the decode reads, writable: bumped by the merge kernel
+    int32_t* seq_len;        // the same array the decode reads, writable: bumped by the merge kernel, or by the
+                             // split launch itself when the merge is folded into it
 };
 // One full-width token per sequence appended to the text segment inside the split kernel.
 struct TextAppendDev {
