@@ -755,7 +755,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
 
     // big: the four waves' O [4][16][128] at the end
     __shared__ __attribute__((aligned(16))) float big[4 * 16 * D];
-    __shared__ __attribute__((aligned(16))) float qt[16][R];
+    __shared__ __attribute__((aligned(16))) float qt[16][R + 4];     // rows 16 bytes apart in the banks: lanes of a wave index the row
     __shared__ float sbias[16];
     __shared__ __attribute__((aligned(16))) float sdm[D];
     __shared__ float sm_m[4][16], sm_l[4][16];
