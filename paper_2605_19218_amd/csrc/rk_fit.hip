@@ -485,6 +485,8 @@ constexpr int EIG_MAX_SWEEPS = 20;
 constexpr int EIG_ROUNDS = D - 1;
 constexpr int EIG_LD = D + 2;             // row stride of the LDS copies of A (even: a 2x2 block is two 8-byte reads)
 constexpr int EIG_ROT_ROUNDS = EIG_MAX_SWEEPS * EIG_ROUNDS;     // recorded rounds per matrix
+constexpr int EIG_FUSE_V_FROM = 192;      // matrices per call from which V is carried inside the A kernel
+                                          // (measured: 128 matrices 1.29 ms carried / 1.17 ms replayed, 256: 1.41 / 1.53, 512: 2.48 / 3.0)
 constexpr size_t EIG_LDS_BYTES = (size_t)(2 * D * EIG_LD + 4 * 64 + 32 + D) * sizeof(float);
 
 // LDS offset of the kept copy of element (r, c) = (c, r): pairs in ascending order, then positions
@@ -543,6 +545,12 @@ __device__ __forceinline__ float lane_from_above(float keep, float v)      // la
 template <bool B>
 struct EigBool { static constexpr bool value = B; };
 
+// WITH_V: the rows of V are updated in this kernel as well (waves 1-15, nine rows each, in registers, as
+// in eig_apply_rotations) and R is written at the end; nothing is recorded.  A round is then bound by
+// vector issue (about 2000 cycles instead of 1400), which pays once there are enough matrices to fill
+// the chip: the replay kernel is throughput-bound, this one is not.
+constexpr int EIGV_FUSED_ROWS = 9;
+template <bool WITH_V>
 __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float* __restrict__ cov,
                                                                     const float* __restrict__ sigma, int r,
                                                                     float* __restrict__ lam_out,
@@ -550,7 +558,8 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
                                                                     int32_t* __restrict__ keep_out,
                                                                     float2* __restrict__ rot,
                                                                     int32_t* __restrict__ sweeps_ws,
-                                                                    int32_t* __restrict__ sweeps_out)
+                                                                    int32_t* __restrict__ sweeps_out,
+                                                                    float* __restrict__ R_out)
 {
     extern __shared__ float sm[];
     float* A2 = sm;                                   // [2][128][129]: the two copies of A
@@ -630,12 +639,23 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
         float tn;
         jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
         prm[lk] = make_float2(ps, ptau);
-        rot_u[lk] = make_float2(ps, ptau);
+        if (!WITH_V) rot_u[lk] = make_float2(ps, ptau);
         dOff = (ps == 0.f) ? apq : 0.f;                    // left as it is when the rotation is skipped
         dE00 = app - tn * apq;
         dE11 = aqq + tn * apq;
     }
     __syncthreads();
+    // WITH_V: wave w >= 1 holds rows 9 (w - 1) .. + 8 of V (rows >= 128 are padding), lane k the elements at
+    // positions 2 k and 2 k + 1
+    float vtop[EIGV_FUSED_ROWS], vbot[EIGV_FUSED_ROWS];
+    const int vrow0 = (wave - 1) * EIGV_FUSED_ROWS;
+    if (WITH_V) {
+#pragma unroll
+        for (int i = 0; i < EIGV_FUSED_ROWS; ++i) {
+            vtop[i] = (wave > 0 && vrow0 + i == 2 * lane) ? 1.f : 0.f;
+            vbot[i] = (wave > 0 && vrow0 + i == 2 * lane + 1) ? 1.f : 0.f;
+        }
+    }
 
     // One round: from copy FROM1 of A to the other one; rotations of this round in prm[FROM1].
     // Rotations are applied as x' = x - s (y + tau x), y' = y + s (x - tau y) with tau = s / (1 + c):
@@ -668,11 +688,13 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
             float tn;
             jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
             pnext[lk] = make_float2(ps, ptau);
-            if (t + 1 < EIG_ROT_ROUNDS) rot_u[(size_t)(t + 1) * 64 + lk] = make_float2(ps, ptau);
+            if (!WITH_V && t + 1 < EIG_ROT_ROUNDS) rot_u[(size_t)(t + 1) * 64 + lk] = make_float2(ps, ptau);
             dOff = (ps == 0.f) ? apq : 0.f;
             dE00 = app - tn * apq;
             dE11 = aqq + tn * apq;
         }
+        float2 pv = make_float2(0.f, 0.f);
+        if (WITH_V && wave != 0) pv = pcur[lane];
         float a[2][4];
         float2 p1[2], p2[2];
 #pragma unroll
@@ -695,6 +717,17 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
             const float xa0 = hi16 ? e01 : e00, xb0 = hi16 ? e00 : e01;
             const float xa1 = hi16 ? e11 : e10, xb1 = hi16 ? e10 : e11;
             if (act[ts]) { nxt[wa[ts][0]] = xa0; nxt[wb[ts][0]] = xb0; nxt[wa[ts][1]] = xa1; nxt[wb[ts][1]] = xb1; }
+        }
+        if (WITH_V && wave != 0) {                      // V <- V J, then the columns move (see eig_apply_rotations)
+            const bool lane1 = lane == 1;
+#pragma unroll
+            for (int i = 0; i < EIGV_FUSED_ROWS; ++i) {
+                const float x = vtop[i], y = vbot[i];
+                const float xn = x - pv.x * (y + pv.y * x), yn = y + pv.x * (x - pv.y * y);
+                const float t_up = lane_from_below(xn, xn), b_up = lane_from_below(yn, yn);
+                vtop[i] = lane1 ? b_up : t_up;
+                vbot[i] = lane_from_above(xn, yn);
+            }
         }
         __syncthreads();
     };
@@ -738,6 +771,12 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
         if (sweeps_out) sweeps_out[u] = sweeps_done;
     }
     if (tid < D) slam[tid] = Af[tid * EIG_LD + tid];
+    if (WITH_V && wave != 0) {
+#pragma unroll
+        for (int i = 0; i < EIGV_FUSED_ROWS; ++i)
+            if (vrow0 + i < D)
+                *(float2*)(R_out + (size_t)u * D * D + (size_t)(vrow0 + i) * D + 2 * lane) = make_float2(vtop[i], vbot[i]);
+    }
     __syncthreads();
     if (tid < D) {
         float lc = slam[tid];
@@ -1234,16 +1273,28 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
                       float* lam, uint8_t* mask, int32_t* keep_idx, float* Rr, float* dmu, int32_t* sweeps,
                       void* rotations, int32_t* sweeps_ws, hipStream_t st)
 {
-    hipError_t e = allow_dynamic_lds((const void*)eig_jacobi_rotations, EIG_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(eig_jacobi_rotations, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, r, lam, mask,
-                       keep_idx, (float2*)rotations, sweeps_ws, sweeps);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(eig_apply_rotations, dim3(D / (4 * EIGV_ROWS), U), dim3(256), 0, st, (const float2*)rotations,
-                       sweeps_ws, R);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    // Few matrices: one compute unit each iterates on A and the whole chip replays the rotations on V.
+    // From three quarters of a chip of matrices on, the replay (throughput-bound) costs more than carrying V along.
+    hipError_t e;
+    if (U >= EIG_FUSE_V_FROM) {
+        e = allow_dynamic_lds((const void*)eig_jacobi_rotations<true>, EIG_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(eig_jacobi_rotations<true>, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, r, lam,
+                           mask, keep_idx, (float2*)rotations, sweeps_ws, sweeps, R);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else {
+        e = allow_dynamic_lds((const void*)eig_jacobi_rotations<false>, EIG_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(eig_jacobi_rotations<false>, dim3(U), dim3(EIG_THREADS), EIG_LDS_BYTES, st, cov, sigma, r, lam,
+                           mask, keep_idx, (float2*)rotations, sweeps_ws, sweeps, R);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(eig_apply_rotations, dim3(D / (4 * EIGV_ROWS), U), dim3(256), 0, st, (const float2*)rotations,
+                           sweeps_ws, R);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     e = allow_dynamic_lds((const void*)eig_finish, EIGF_LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(eig_finish, dim3(U), dim3(256), EIGF_LDS_BYTES, st, r, R, keep_idx, mu, Rr, dmu);

@@ -150,6 +150,34 @@ def test_eig_invariants_and_mask(ctx, with_sigma):
     assert torch.equal(Rr2, p.Rr)
 
 
+def test_eig_many_matrices_carry_v(ctx):
+    """From 192 matrices per call the eigensolver carries V inside the kernel that iterates on A (below
+    that it records the rotations and replays them on V in a second kernel).  Same rotations, same
+    arithmetic on V: a batch of 192 heads must give bit for bit what its two halves of 96 give, and the
+    solver invariants hold on sampled heads."""
+    B, Hkv, L, r = 24, 8, 160, 24
+    data = layer(B, Hkv, Hkv, L, "bf16", 14)
+    Kd = to_dev(data["K"], "bf16")
+    full = Pipeline(ctx, B, Hkv, Hkv, r, "bf16", L)
+    full.fit(Kd, L)
+    R, lam, sweeps = to_host(full.R), to_host(full.lam), full.sweeps.cpu().numpy()
+    assert sweeps.min() >= 1 and sweeps.max() < 20
+    for half in range(2):
+        sl = slice(12 * half, 12 * half + 12)
+        p = Pipeline(ctx, 12, Hkv, Hkv, r, "bf16", L)
+        p.fit(Kd[sl].contiguous(), L)
+        assert np.array_equal(to_host(p.lam), lam[sl]) and np.array_equal(to_host(p.R), R[sl])
+        assert np.array_equal(p.sweeps.cpu().numpy(), sweeps[sl])
+        assert torch.equal(p.Rr, full.Rr[sl]) and torch.equal(p.dmu, full.dmu[sl]) and torch.equal(p.mask, full.mask[sl])
+    cov = to_host(full.cov)
+    for b, h in ((0, 0), (7, 3), (23, 7), (13, 5)):
+        Rm, lm, C = R[b, h], lam[b, h], cov[b, h]
+        assert np.abs(Rm.T @ Rm - np.eye(D)).max() <= 1e-5
+        assert np.linalg.norm(Rm.T @ C @ Rm - np.diag(lm)) <= 1e-5 * np.linalg.norm(C)
+        lam_o = np.linalg.eigvalsh(C)[::-1]
+        assert np.abs(np.sort(lm)[::-1] - lam_o).max() <= 1e-5 * lam_o[0]
+
+
 def test_eig_degenerate_inputs(ctx):
     """Covariances the sweep loop must leave alone or handle without a rotation to find: all-zero Keys
     (no sweep at all: R = I, every eigenvalue 0), Keys along the coordinate axes (a diagonal covariance:
