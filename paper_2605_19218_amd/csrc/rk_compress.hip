@@ -85,8 +85,12 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
     const int n_b = min(rows_count(rows, b), cap);
-    if (blockIdx.x == 0 && h == 0 && tid == 0 && seq_len_out) seq_len_out[b] = n_b;
-    const int blk0 = blockIdx.x * Cfg::TOK_PER_BLOCK;
+    // Work-groups go to the 8 XCDs round-robin by linear index, i.e. by blockIdx.x when the grid's first
+    // extent is a multiple of 8: the block number is rotated by head and batch item, so that an XCD
+    // does not end up with "block 7 of every sequence" (which only the longest sequences have)
+    const int bx = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
+    if (bx == 0 && h == 0 && tid == 0 && seq_len_out) seq_len_out[b] = n_b;
+    const int blk0 = bx * Cfg::TOK_PER_BLOCK;
     if (blk0 >= n_b) return;
 
     const bf16_t* base = (const bf16_t*)rows.data;
@@ -206,12 +210,14 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
     __builtin_amdgcn_sched_barrier(0);
 
     const int w_first = blk0 + wave * (Cfg::TT * 16);
-    if (blk0 + Cfg::TOK_PER_BLOCK <= n_b) {
-        // Full block (the normal case): passes in pairs, the Key rows of pass p + 1 requested
-        // before pass p is rotated, the first pass before R_r is even split -- R_r's loads are
-        // older than the Key loads, so the wait for them does not wait for Keys.  The trip count
-        // is a constant and nothing is loaded conditionally: every wait on a load is exact.
-        static_assert(Cfg::PASSES % 2 == 0 && Cfg::PASSES >= 4, "passes are taken in pairs");
+    // Passes in pairs, the Key rows of pass p + 1 requested before pass p is rotated, the first pass
+    // before R_r is even split -- R_r's loads are older than the Key loads, so the wait for them does
+    // not wait for Keys.  Nothing is loaded conditionally (rows past the end are clamped to the last
+    // row and never stored) and the trip count is uniform, so every wait on a load is exact.  A full
+    // block makes PASSES passes; the ragged last block of a sequence makes as many as it has rows for,
+    // rounded up to a pair.
+    static_assert(Cfg::PASSES % 2 == 0 && Cfg::PASSES >= 4, "passes are taken in pairs");
+    auto run_block = [&](auto full, int np2) {
         constexpr int TP = Cfg::TOK_PER_PASS;
         bf16x8 ka[Cfg::TT][4], kc[Cfg::TT][4];
         if (!GATHER) {
@@ -220,18 +226,18 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
             park_fragments();
             __syncthreads();
 #pragma unroll 1
-            for (int p = 0; p < Cfg::PASSES - 2; p += 2) {
+            for (int p = 0; p < np2 - 2; p += 2) {
                 load_keys(kc, w_first + (p + 1) * TP);
                 __builtin_amdgcn_sched_barrier(0);
-                rotate_store(ka, w_first + p * TP, std::true_type{});
+                rotate_store(ka, w_first + p * TP, full);
                 load_keys(ka, w_first + (p + 2) * TP);
                 __builtin_amdgcn_sched_barrier(0);
-                rotate_store(kc, w_first + (p + 1) * TP, std::true_type{});
+                rotate_store(kc, w_first + (p + 1) * TP, full);
             }
-            load_keys(kc, w_first + (Cfg::PASSES - 1) * TP);
+            load_keys(kc, w_first + (np2 - 1) * TP);
             __builtin_amdgcn_sched_barrier(0);
-            rotate_store(ka, w_first + (Cfg::PASSES - 2) * TP, std::true_type{});
-            rotate_store(kc, w_first + (Cfg::PASSES - 1) * TP, std::true_type{});
+            rotate_store(ka, w_first + (np2 - 2) * TP, full);
+            rotate_store(kc, w_first + (np2 - 1) * TP, full);
             return;
         }
         // With a token list a row's address comes from a load.  The row numbers of pass p + 2 are
@@ -247,34 +253,25 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
         park_fragments();
         __syncthreads();
 #pragma unroll 1
-        for (int p = 0; p < Cfg::PASSES - 2; p += 2) {
+        for (int p = 0; p < np2 - 2; p += 2) {
             load_rows_idx(ia, w_first + (p + 2) * TP);
             __builtin_amdgcn_sched_barrier(0);
             load_keys_at(kc, ic);
             __builtin_amdgcn_sched_barrier(0);
-            rotate_store(ka, w_first + p * TP, std::true_type{});
-            load_rows_idx(ic, w_first + min(p + 3, Cfg::PASSES - 1) * TP);
+            rotate_store(ka, w_first + p * TP, full);
+            load_rows_idx(ic, w_first + min(p + 3, np2 - 1) * TP);
             __builtin_amdgcn_sched_barrier(0);
             load_keys_at(ka, ia);
             __builtin_amdgcn_sched_barrier(0);
-            rotate_store(kc, w_first + (p + 1) * TP, std::true_type{});
+            rotate_store(kc, w_first + (p + 1) * TP, full);
         }
         load_keys_at(kc, ic);
         __builtin_amdgcn_sched_barrier(0);
-        rotate_store(ka, w_first + (Cfg::PASSES - 2) * TP, std::true_type{});
-        rotate_store(kc, w_first + (Cfg::PASSES - 1) * TP, std::true_type{});
-        return;
-    }
-    // ragged last block of a sequence: one pass at a time
-    park_fragments();
-    __syncthreads();
-    for (int pass = 0; pass < Cfg::PASSES; ++pass) {
-        const int w0 = w_first + pass * Cfg::TOK_PER_PASS;
-        if (w0 >= n_b) return;                      // later passes start even further right
-        bf16x8 kb[Cfg::TT][4];
-        load_keys(kb, w0);
-        rotate_store(kb, w0, std::false_type{});
-    }
+        rotate_store(ka, w_first + (np2 - 2) * TP, full);
+        rotate_store(kc, w_first + (np2 - 1) * TP, full);
+    };
+    const int rows_here = min(n_b - blk0, Cfg::TOK_PER_BLOCK);
+    run_block(std::false_type{}, (((rows_here + Cfg::TOK_PER_PASS - 1) / Cfg::TOK_PER_PASS) + 1) & ~1);
 }
 
 // ---------------------------------------------------------------------------

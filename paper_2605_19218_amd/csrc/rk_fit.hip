@@ -232,7 +232,11 @@ template <bool GATHER>
 __global__ __launch_bounds__(256) void cov_partial_mfma(RowsDev rows, int Hkv, int n_chunks,
                                                         float* __restrict__ part_S, float* __restrict__ part_sum)
 {
-    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // the chunk number is rotated by head and batch item: with a chunk count that is a multiple of 8 an
+    // XCD (work-groups are dealt to the XCDs by linear index) would otherwise own one chunk position of
+    // every sequence, and ragged batches have few sequences with the last positions
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int chunk = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
     const int u = b * Hkv + h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: loop control stays scalar
