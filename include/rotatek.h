@@ -15,6 +15,10 @@
  *     only device memory of its own is what a context holds from rk_create to
  *     rk_destroy (512 KB of counters) and the fixed scratch array behind
  *     rk_decode_attn_static; no other call allocates or frees.
+ *   - A context holds small device counters that rk_append, rk_decode_attn and
+ *     rk_append_decode_attn use and leave at zero.  Calls on ONE context must
+ *     therefore not overlap in time on the GPU (use one stream per context, or
+ *     one context per stream); calls on different contexts are independent.
  *   - All kernels are enqueued on the caller's stream (`stream` is a
  *     hipStream_t passed as void*; NULL = the default stream).  Calls are
  *     asynchronous.  Argument validation is synchronous and precedes any launch.
