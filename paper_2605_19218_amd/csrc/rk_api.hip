@@ -151,8 +151,10 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_o
         // one 4-wave work-group per compute unit: a second one gets its memory requests served only
         // after the first one's (measured: its prologue then ends 10 us later), and every work-group
         // pays its own prologue and partial
+        // (rounded down: a few work-groups more than compute units would run as a second round)
         long target = n_cu;
-        S = (int)((target + units - 1) / units);
+        S = (int)(target / units);
+        if (S < 1) S = 1;
         if (S > 64) S = 64;
         // a split shorter than 512 tokens (four 32-token tiles per wave) no longer amortises its
         // prologue and its partial: measured optimum on short caches and small batches.  Very short

@@ -1257,11 +1257,15 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         dim3 grid(S, Hkv * ngrp, B);                    // visual splits only: (split, (h_kv, head group), b)
         if (TS > 0)                                     // one dimension: the splits, then the text work-groups
             grid = dim3((unsigned)(((n_vis + 7) & ~7) + (G < 16 ? G : 16) * ((nunit * TS + 7) & ~7)));
-        // Merge folded into the split launch: a plain decode with several splits whose units deal
-        // out evenly over the 8 XCDs (the splits of a unit share an XCD there; an uneven deal would
-        // leave XCDs idle, which costs more than the second launch saves)
+        // Merge folded into the split launch: the splits of a unit share an XCD there, so a unit count
+        // that is not a multiple of 8 loads the XCDs unevenly (4 units: half of them idle).  The busiest
+        // XCD then streams ceil(nunit / 8) * 8 / nunit times its fair share; folded is chosen while that
+        // excess, priced at the chip's streaming rate, stays below what the second launch costs
+        // (measured: 4 units x 4K tokens 9.8 us folded against 11.6 us, 4 units x 16K tokens 14.6 against 13.5 us).
+        const double cache_bytes = (double)nunit * tiles_all * 128.0 * (keep_padded(r) + D) * 2.0;
+        const double excess_us = ((double)((nunit + 7) / 8 * 8) / nunit - 1.0) * cache_bytes / 6.5e6;
         const bool fused_merge = !text && (!app || batch_tickets) && S >= 2 && counters && nunit <= n_counters &&
-                                 (nunit % 8 == 0 || nunit >= 160);
+                                 excess_us < 3.0;
         if (fused_merge) {
             grid = dim3((unsigned)(8 * ((nunit + 7) / 8) * S));
             n_vis = nunit;
