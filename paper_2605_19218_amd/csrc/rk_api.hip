@@ -154,7 +154,16 @@ void decode_plan(const rk_ctx* ctx, const rk_layout* L, int* S_out, int* tiles_o
         // (rounded down: a few work-groups more than compute units would run as a second round)
         long target = n_cu;
         S = (int)(target / units);
-        if (S < 1) S = 1;
+        if (S < 1) {
+            // more units than compute units: a partly filled last round costs a whole round (320 units:
+            // 186 us unsplit, 162 us with four splits); take the split count 1..4 that wastes least of it
+            S = 1;
+            double best = 1e30;
+            for (int c = 1; c <= 4; ++c) {
+                const double cost = (double)((units * c + target - 1) / target) / c;
+                if (cost < best - 1e-9) { best = cost; S = c; }
+            }
+        }
         if (S > 64) S = 64;
         // a split shorter than 512 tokens (four 32-token tiles per wave) no longer amortises its
         // prologue and its partial: measured optimum on short caches and small batches.  Very short
