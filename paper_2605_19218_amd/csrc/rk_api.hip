@@ -594,7 +594,7 @@ static rk_status decode_common(rk_ctx* ctx, const rk_layout* L, const void* q, c
                       L->keep, S, tiles, q, k_packed, v_cache, R_r, delta_mu, L->seq_len, text ? &td : nullptr, nullptr,
                       tk_new ? &ta : nullptr, sc, out, (float*)workspace,
                       ctx->fuse_merge && ctx->xcd_deal_ok ? ctx->tickets + APP_TICKETS : nullptr, DEC_COUNTERS,
-                      nullptr, as_stream(stream));
+                      L->batch <= APP_TICKETS ? ctx->tickets : nullptr, as_stream(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "decode launch");
     return RK_OK;
 }

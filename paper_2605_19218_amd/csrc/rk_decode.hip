@@ -645,6 +645,81 @@ __device__ __forceinline__ void fold_partials(const float* pm, const float* pl, 
     }
 }
 
+// App. C phase 2 inside the split launch: called by every work-group of a unit (one (b, h_kv, head
+// group)) once its partial is stored; the one that arrives last folds the unit's partials.
+// Vector stores stay counted until the L2 has acknowledged them, so after the wait and the barrier
+// every partial of this work-group is in the XCD's L2, and the counter increment that follows is
+// ordered behind them.  All work-groups of a unit run on one XCD (see the index mapping in the
+// kernel), so the one that draws the last ticket finds all partials in that same L2; it has never
+// read those lines before, so its L1 holds nothing stale.  The fold runs in slot order, whoever
+// does it.  `bump`: this launch also appends a row (rotated cache: NEW = true, the row's own score in
+// snew and its Values in v_new enter as one more term; text segment: NEW = false, the text
+// work-groups already counted it); the length of batch item b moves once every work-group of the
+// item -- they sit on different XCDs, hence a second, device-wide set of tickets -- has taken one,
+// i.e. has read the old length and is done with it.
+template <bool NEW>
+__device__ __forceinline__ void fold_unit(int unit, int unit_parts, int n_slots, int SP, int b, int u, int Hq, int h0,
+                                          int Gc, const float* ws_m, const float* ws_l, const float* ws_acc,
+                                          bf16_t* __restrict__ out_merged, int32_t* done, bool bump,
+                                          int32_t* batch_tickets, int batch_wgs, int32_t* len_rw, int len_cap,
+                                          const float* snew, const bf16_t* __restrict__ v_new, int* sm_last)
+{
+    const int tid = threadIdx.x;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) {
+        *sm_last = __hip_atomic_fetch_add(done + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == unit_parts - 1;
+        if (bump &&
+            __hip_atomic_fetch_add(batch_tickets + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == batch_wgs - 1) {
+            batch_tickets[b] = 0;
+            const int len = len_rw[b];
+            if (len >= 0 && len < len_cap) len_rw[b] = len + 1;
+        }
+    }
+    __syncthreads();
+    if (!*sm_last) return;
+    const int hh = tid >> 4, c0 = (tid & 15) * 8;           // thread = (head, 8 channels)
+    if (hh < Gc) {
+        const size_t row = (size_t)b * Hq + h0 + hh;
+        const float* pm = ws_m + row * SP;
+        const float* pl = ws_l + row * SP;
+        const float* pa = ws_acc + row * SP * D + c0;
+        float M = NEG_INF, den = 0.f;
+        f32x4 n0 = (f32x4){0.f, 0.f, 0.f, 0.f}, n1 = n0;
+        float sx = NEG_INF;
+        uint4 vraw = make_uint4(0, 0, 0, 0);
+        if (NEW && snew) {                                   // the appended token: one more term of the softmax
+            sx = snew[row];
+            vraw = *(const uint4*)(v_new + (size_t)u * D + c0);
+        }
+        if (n_slots <= 8) fold_partials<8>(pm, pl, pa, n_slots, M, den, n0, n1);     // one round trip to the L2
+        else fold_partials<16>(pm, pl, pa, n_slots, M, den, n0, n1);
+        if (NEW && sx > NEG_INF) {
+            const float Mc = fmaxf(M, sx);
+            const float resc = exp2f(M - Mc), w = exp2f(sx - Mc);
+            const uint32_t vw[4] = {vraw.x, vraw.y, vraw.z, vraw.w};
+            den = fmaf(den, resc, w);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = bf16_to_f32((bf16_t)(vw[e >> 1] >> (16 * (e & 1))));
+                const float hi = bf16_to_f32((bf16_t)(vw[2 + (e >> 1)] >> (16 * (e & 1))));
+                n0[e] = fmaf(n0[e], resc, lo * w);
+                n1[e] = fmaf(n1[e], resc, hi * w);
+            }
+            M = Mc;
+        }
+        const float inv = (M > NEG_INF) ? 1.f / den : 0.f;
+        uint4 pk;
+        pk.x = (uint32_t)f32_to_bf16(n0[0] * inv) | ((uint32_t)f32_to_bf16(n0[1] * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(n0[2] * inv) | ((uint32_t)f32_to_bf16(n0[3] * inv) << 16);
+        pk.z = (uint32_t)f32_to_bf16(n1[0] * inv) | ((uint32_t)f32_to_bf16(n1[1] * inv) << 16);
+        pk.w = (uint32_t)f32_to_bf16(n1[2] * inv) | ((uint32_t)f32_to_bf16(n1[3] * inv) << 16);
+        *(uint4*)(out_merged + row * D + c0) = pk;
+    }
+    __syncthreads();
+    if (tid == 0) done[unit] = 0;                           // ready for the next launch on this context
+}
+
 template <int R>
 struct DecState {
     float m_run, l_run;
@@ -778,8 +853,22 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         // partials without any device-wide cache write-back (n_vis = number of units here; the host
         // checks the deal once per context, see rk_create).  Units go fastest inside an XCD's slots, so
         // every unit has work-groups among the first dispatched and among the last.
-        const int id = blockIdx.x, slot = id >> 3, upx = (n_vis + 7) >> 3, ul = slot % upx;
-        split = slot / upx;
+        const int id = blockIdx.x, upx = (n_vis + 7) >> 3;
+        int slot = id >> 3, ul;
+        if (!TEXT || slot < upx * S) {
+            ul = slot % upx;
+            split = slot / upx;
+        } else {
+            // text work-groups of the dual path, behind the visual ones: (unit, slice, head) with the head
+            // fastest, on the unit's XCD like its splits; the heads of a group read the same rows at about
+            // the same time and share the XCD's L2
+            slot -= upx * S;
+            const int Gm = min(G, 16), item = slot / upx;
+            ul = slot % upx;
+            tgin = item % Gm;
+            tslice = item / Gm;
+            split = 0;
+        }
         unit = 8 * ul + (id & 7);
         if (unit >= n_vis) return;
         const int gy = Hkv * ngrp;
@@ -816,12 +905,19 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int u = b * Hkv + hk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
+    // FUSED: partials a unit collects (its splits, and with TEXT one per head and text slice) and the
+    // work-groups of a batch item (all of them take a ticket before the item's lengths may move)
+    const int unit_parts = S + (TEXT ? TS * Gc : 0);
+    const int batch_wgs = Hkv * (ngrp * S + (TEXT ? TS * G : 0));
     if (TEXT && tgin >= 0) {                   // a text work-group: one query head, one slice of the rows
-        if (tgin < Gc) {
-            const size_t row = (size_t)b * Hq + h0 + tgin;
-            text_partial(q, text, ta, tgin == 0 && grp == 0, b, hk, Hkv, row, tslice, TS, scale_log2, ws_m, ws_l,
-                         ws_acc, row * SP + S + tslice, big);
-        }
+        if (tgin >= Gc) return;
+        const size_t row = (size_t)b * Hq + h0 + tgin;
+        text_partial(q, text, ta, tgin == 0 && grp == 0, b, hk, Hkv, row, tslice, TS, scale_log2, ws_m, ws_l,
+                     ws_acc, row * SP + S + tslice, big);
+        if constexpr (FUSED)
+            fold_unit<false>(unit, unit_parts, S + TS, SP, b, u, Hq, h0, Gc, ws_m, ws_l, ws_acc, out_merged, done,
+                             ta.k != nullptr, batch_tickets, batch_wgs, ta.len, min(ta.capacity, text.max_len),
+                             nullptr, nullptr, &sm_last);
         return;
     }
 
@@ -1118,68 +1214,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     }
 
     if constexpr (FUSED) {
-        // ---- App. C phase 2 inside the split launch: the unit's last work-group folds the partials ----
-        // Vector stores stay counted until the L2 has acknowledged them, so after this wait and the
-        // barrier every partial of this work-group is in the XCD's L2, and the counter increment that
-        // follows is ordered behind them.  The S work-groups of a unit run on one XCD (see the index
-        // mapping above), so the one that draws the last ticket finds all S partials in that same L2.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) {
-            sm_last = __hip_atomic_fetch_add(done + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == S - 1;
-            if (STEP && app) {
-                // Fused append: the length of sequence b moves once every work-group of the batch item
-                // (all units, all splits: they sit on different XCDs, hence a device-wide counter) has
-                // read the old one and is done with it; whoever draws the item's last ticket does it.
-                const int all = Hkv * ngrp * S;
-                if (__hip_atomic_fetch_add(batch_tickets + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == all - 1) {
-                    batch_tickets[b] = 0;
-                    if (app_ok) seq_len_rw[b] = seq_raw + 1;
-                }
-            }
-        }
-        __syncthreads();
-        if (!sm_last) return;
-        const int hh = tid >> 4, c0 = (tid & 15) * 8;           // thread = (head, 8 channels)
-        if (hh < Gc) {
-            const size_t row = (size_t)b * Hq + h0 + hh;
-            const float* pm = ws_m + row * SP;
-            const float* pl = ws_l + row * SP;
-            const float* pa = ws_acc + row * SP * D + c0;
-            float M = NEG_INF, den = 0.f;
-            f32x4 n0 = (f32x4){0.f, 0.f, 0.f, 0.f}, n1 = n0;
-            float sx = NEG_INF;
-            uint4 vraw = make_uint4(0, 0, 0, 0);
-            if (STEP && app) {                                   // the appended token: one more term of the softmax
-                sx = ws_snew[row];
-                vraw = *(const uint4*)(v_new + (size_t)u * D + c0);
-            }
-            if (S <= 8) fold_partials<8>(pm, pl, pa, S, M, den, n0, n1);     // one round trip to the L2
-            else fold_partials<16>(pm, pl, pa, S, M, den, n0, n1);
-            if (STEP && sx > NEG_INF) {
-                const float Mc = fmaxf(M, sx);
-                const float resc = exp2f(M - Mc), w = exp2f(sx - Mc);
-                const uint32_t vw[4] = {vraw.x, vraw.y, vraw.z, vraw.w};
-                den = fmaf(den, resc, w);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float lo = bf16_to_f32((bf16_t)(vw[e >> 1] >> (16 * (e & 1))));
-                    const float hi = bf16_to_f32((bf16_t)(vw[2 + (e >> 1)] >> (16 * (e & 1))));
-                    n0[e] = fmaf(n0[e], resc, lo * w);
-                    n1[e] = fmaf(n1[e], resc, hi * w);
-                }
-                M = Mc;
-            }
-            const float inv = (M > NEG_INF) ? 1.f / den : 0.f;
-            uint4 pk;
-            pk.x = (uint32_t)f32_to_bf16(n0[0] * inv) | ((uint32_t)f32_to_bf16(n0[1] * inv) << 16);
-            pk.y = (uint32_t)f32_to_bf16(n0[2] * inv) | ((uint32_t)f32_to_bf16(n0[3] * inv) << 16);
-            pk.z = (uint32_t)f32_to_bf16(n1[0] * inv) | ((uint32_t)f32_to_bf16(n1[1] * inv) << 16);
-            pk.w = (uint32_t)f32_to_bf16(n1[2] * inv) | ((uint32_t)f32_to_bf16(n1[3] * inv) << 16);
-            *(uint4*)(out_merged + row * D + c0) = pk;
-        }
-        __syncthreads();
-        if (tid == 0) done[unit] = 0;                           // ready for the next launch on this context
+        const bool bump = STEP ? app : (TEXT && ta.k != nullptr);
+        fold_unit<STEP>(unit, unit_parts, S + (TEXT ? TS : 0), SP, b, u, Hq, h0, Gc, ws_m, ws_l, ws_acc, out_merged, done,
+                        bump, batch_tickets, batch_wgs, STEP ? seq_len_rw : ta.len,
+                        STEP ? cap : min(ta.capacity, text.max_len), STEP && app ? ws_snew : nullptr, v_new, &sm_last);
     }
 }
 
@@ -1194,7 +1232,11 @@ static void launch_decode_mfma_r(dim3 grid, hipStream_t st, const bf16_t* q, bf1
                                  const TextDev& text, int TS, int SP, int n_vis, bf16_t* out_merged, int32_t* done,
                                  int32_t* batch_tickets, int32_t* seq_len_rw)
 {
-    if (out_merged && k_new)
+    if (out_merged && TS > 0)
+        hipLaunchKernelGGL((decode_split_mfma<R, false, true, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
+                           seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
+                           SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
+    else if (out_merged && k_new)
         hipLaunchKernelGGL((decode_split_mfma<R, true, false, true>), grid, dim3(256), 0, st, q, Kp, Vc, Rr, dmu,
                            seq_len, Hq, Hkv, cap, r, tiles_all, sl2, m, l, acc, S, out, k_new, v_new, snew, ta, text, TS,
                            SP, n_vis, out_merged, done, batch_tickets, seq_len_rw);
@@ -1264,10 +1306,11 @@ hipError_t launch_decode(int dtype, bool mfma, int B, int Hq, int Hkv, int cap, 
         // (measured: 4 units x 4K tokens 9.8 us folded against 11.6 us, 4 units x 16K tokens 14.6 against 13.5 us).
         const double cache_bytes = (double)nunit * tiles_all * 128.0 * (keep_padded(r) + D) * 2.0;
         const double excess_us = ((double)((nunit + 7) / 8 * 8) / nunit - 1.0) * cache_bytes / 6.5e6;
-        const bool fused_merge = !text && (!app || batch_tickets) && S >= 2 && counters && nunit <= n_counters &&
-                                 excess_us < 3.0;
+        // (with a text segment the partials of the text work-groups join the same fold, so there S = 1 folds too)
+        const bool fused_merge = (!text || TS > 0) && ((!app && !tapp) || batch_tickets) && (S >= 2 || TS > 0) && counters &&
+                                 nunit <= n_counters && excess_us < 3.0;
         if (fused_merge) {
-            grid = dim3((unsigned)(8 * ((nunit + 7) / 8) * S));
+            grid = dim3((unsigned)(8 * ((nunit + 7) / 8) * (S + TS * (G < 16 ? G : 16))));
             n_vis = nunit;
         }
         const bf16_t* q_ = (const bf16_t*)q;

@@ -98,13 +98,18 @@ def test_dual_decode_parity(ctx, case):
         got_nobias = decode_dual(ctx, p, q, seg.arg(), use_bias=False)
         again = decode_dual(ctx, p, q, seg.arg())
         single = p.decode(q).copy()
+        # the same call with the separate merge launch (where the merge is folded into the split launch)
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 0)
+        two_launch = decode_dual(ctx, p, q, seg.arg())
     finally:
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 1)
         rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
         rk.rk_set_option(ctx, rk.RK_OPT_DECODE_SPLITS, 0)
     want = oracle_dual(p, data["q"], lens, seg, lens_t)
     want_nobias = oracle_dual(p, data["q"], lens, seg, lens_t, use_bias=False)
     check_out(got, want, dtype)
     check_out(got_nobias, want_nobias, dtype)
+    check_out(two_launch, want, dtype)
     assert np.array_equal(got, again)
     for b in range(B):
         if lens[b] == 0 and lens_t[b] == 0:

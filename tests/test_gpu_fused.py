@@ -206,8 +206,11 @@ TEXT_FUSED_CASES = [
 ]
 
 
+@pytest.mark.parametrize("fold", [1, 0], ids=["merge_folded", "merge_launch"])
 @pytest.mark.parametrize("case", TEXT_FUSED_CASES, ids=[c[0] for c in TEXT_FUSED_CASES])
-def test_append_text_decode_fused(ctx, case):
+def test_append_text_decode_fused(ctx, case, fold):
+    """`fold`: with the split-K merge folded into the split launch where the shape allows it (the text length
+    is then bumped by the batch item's last work-group), and with the separate merge launch."""
     _, dtype, B, Hq, Hkv, L, lengths, r, lens_t, generic, stride = case
     steps, cap_t = 5, max(lens_t) + 5
     data = layer(B, Hq, Hkv, L, dtype, 64, lengths=lengths, mean_shift=1.5)
@@ -219,6 +222,7 @@ def test_append_text_decode_fused(ctx, case):
     ref.fill(tdata["K"], tdata["V"])
     lens_t = list(lens_t)
     rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, int(generic))
+    rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, fold)
     try:
         for step in range(steps):
             new = layer(B, Hq, Hkv, 1, dtype, 6400 + step)
@@ -240,6 +244,7 @@ def test_append_text_decode_fused(ctx, case):
             assert torch.equal(seg.k, ref.k) and torch.equal(seg.v, ref.v)
     finally:
         rk.rk_set_option(ctx, rk.RK_OPT_FORCE_GENERIC, 0)
+        rk.rk_set_option(ctx, rk.RK_OPT_FUSE_MERGE, 1)
     assert seg.max_len == cap_t
     with pytest.raises(rk.RotateKError) as e:
         fused_dual(ctx, p, kn, vn, q, seg.arg())
