@@ -327,10 +327,11 @@ rk_status rk_append_decode_attn(rk_ctx* ctx, const rk_layout* L, const void* k_n
  * bias), and ONE softmax runs over the concatenation [s_vis; s_pt]; out =
  * P [V_vis; V_pt].  The bias therefore matters here: it shifts the visual
  * scores against the text scores.  Either segment may be empty per sequence;
- * both empty yields zeros.  Always two launches.  On the matrix-core path the
- * text attention runs in extra work-groups of the split-K launch, in slices of
- * about 512 rows that each leave a partial of their own, and the merge kernel
- * folds visual and text partials alike; with fp32 storage or the plain kernels
+ * both empty yields zeros.  On the matrix-core path the text attention runs in
+ * extra work-groups of the split-K launch, in slices of about 512 rows that
+ * each leave a partial of their own, and visual and text partials are folded
+ * alike, inside that launch where rk_decode_attn folds its own, else by the
+ * merge kernel; with fp32 storage or the plain kernels
  * the second kernel runs the text attention itself and then folds the visual
  * partials (the fusion App. C describes).  Same workspace as rk_decode_attn.
  * Errors: as rk_decode_attn, plus INVALID_ARG for a malformed `text`
@@ -355,8 +356,8 @@ rk_status rk_append_text(rk_ctx* ctx, const rk_layout* L, const rk_text* text, c
  * K_pt): row len[b] of text->k / text->v receives k_new / v_new [B,H_kv,d],
  * len[b] += 1 on the device, and the softmax of this step already includes the
  * new row.  Same results as the two calls (the rows are copied, the attention
- * arithmetic is the same code); the same two launches as rk_decode_attn_dual,
- * the copy riding in the first.  text->len must be given; text->max_len bounds
+ * arithmetic is the same code); the same launches as rk_decode_attn_dual, the
+ * copy riding in the first.  text->len must be given; text->max_len bounds
  * len[b] BEFORE the call.  k_new, v_new 16-byte aligned.  A sequence whose text
  * segment is already full is left untouched and attends over what it has.
  * Errors: as rk_decode_attn_dual, plus CAPACITY if text->max_len + 1 >
