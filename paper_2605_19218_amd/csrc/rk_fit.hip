@@ -430,9 +430,17 @@ __global__ __launch_bounds__(256) void cov_finalize_tiled(RowsDev rows, int Hkv,
 #pragma unroll
     for (int k = 0; k < 8; ++k) v0[k] = pS[(size_t)min(k, first - 1) * (D * D)];
     if (tid < D) {
+        // column sums of the chunks, eight loads in flight at a time (one at a time this loop was most of
+        // the kernel: eight dependent round trips), added in ascending chunk order
         const float* ps = part_sum + (size_t)u * n_chunks * D + tid;
         double s = 0.0;
-        for (int ch = 0; ch < n_chunks; ++ch) s += (double)ps[(size_t)ch * D];
+        for (int ch = 0; ch < n_chunks; ch += 8) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = ps[(size_t)min(ch + k, n_chunks - 1) * D];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += ch + k < n_chunks ? (double)v[k] : 0.0;
+        }
         const double m = n_b > 0 ? s / (double)n_b : 0.0;
         smu[tid] = m;
         if (blockIdx.x == 0) mu_out[(size_t)u * D + tid] = (float)m;
@@ -855,20 +863,22 @@ __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restr
 // R_r = R[:, keep] and delta_mu = mu - R_r R_r^T mu (Alg. 1 step 14 and 16), one work-group per matrix;
 // R is staged in LDS (row stride 129) so that the column reads below do not go to memory one by one.
 constexpr int EIGF_LD = D + 1;
-constexpr size_t EIGF_LDS_BYTES = (size_t)(D * EIGF_LD + 2 * D + 2 * D) * sizeof(float) + D * sizeof(int);
-__global__ __launch_bounds__(256) void eig_finish(int r, const float* __restrict__ R, const int32_t* __restrict__ keep_idx,
-                                                  const float* __restrict__ mu_in, float* __restrict__ Rr_out,
-                                                  float* __restrict__ dmu_out)
+constexpr int EIGF_THREADS = 1024, EIGF_PARTS = EIGF_THREADS / D;
+constexpr size_t EIGF_LDS_BYTES = (size_t)(D * EIGF_LD + EIGF_PARTS * D + 2 * D) * sizeof(float) + D * sizeof(int);
+__global__ __launch_bounds__(EIGF_THREADS) void eig_finish(int r, const float* __restrict__ R,
+                                                           const int32_t* __restrict__ keep_idx,
+                                                           const float* __restrict__ mu_in, float* __restrict__ Rr_out,
+                                                           float* __restrict__ dmu_out)
 {
     extern __shared__ float fsm[];
     float* Vs = fsm;                          // [128][129]
-    float* part = Vs + D * EIGF_LD;           // [2][128] partial sums
-    float* sw = part + 2 * D;                 // [128] R_r^T mu
+    float* part = Vs + D * EIGF_LD;           // [parts][128] partial sums
+    float* sw = part + EIGF_PARTS * D;        // [128] R_r^T mu
     float* smu = sw + D;                      // [128]
     int* skeep = (int*)(smu + D);             // [128]
     const int u = blockIdx.x, tid = threadIdx.x;
     const float* V = R + (size_t)u * D * D;
-    for (int idx = tid; idx < D * D / 4; idx += 256) {
+    for (int idx = tid; idx < D * D / 4; idx += EIGF_THREADS) {
         const float4 v = *(const float4*)(V + 4 * idx);
         float* d = Vs + (idx >> 5) * EIGF_LD + 4 * (idx & 31);
         d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
@@ -876,30 +886,41 @@ __global__ __launch_bounds__(256) void eig_finish(int r, const float* __restrict
     if (tid < D) smu[tid] = mu_in[(size_t)u * D + tid];
     if (tid < r) skeep[tid] = min(max(keep_idx[(size_t)u * r + tid], 0), D - 1);
     __syncthreads();
-    for (int idx = tid; idx < D * r; idx += 256) {
+    for (int idx = tid; idx < D * r; idx += EIGF_THREADS) {
         int c = idx / r, j = idx - c * r;
         Rr_out[(size_t)u * D * r + idx] = Vs[c * EIGF_LD + skeep[j]];
     }
-    const int half = tid >> 7, x = tid & (D - 1);
-    {                                          // w_j = sum_c V[c][keep_j] mu[c], rows split in two halves
+    const int pt = tid >> 7, x = tid & (D - 1);
+    {                                          // w_j = sum_c V[c][keep_j] mu[c], the rows in EIGF_PARTS ranges
         float w = 0.f;
         if (x < r) {
             const int col = skeep[x];
-            for (int c = 64 * half; c < 64 * half + 64; ++c) w = fmaf(Vs[c * EIGF_LD + col], smu[c], w);
+            constexpr int RP = D / EIGF_PARTS;
+            for (int c = RP * pt; c < RP * pt + RP; ++c) w = fmaf(Vs[c * EIGF_LD + col], smu[c], w);
         }
-        part[half * D + x] = w;
+        part[pt * D + x] = w;
     }
     __syncthreads();
-    if (tid < r) sw[tid] = part[tid] + part[D + tid];
+    if (tid < r) {
+        float w = 0.f;
+#pragma unroll
+        for (int k = 0; k < EIGF_PARTS; ++k) w += part[k * D + tid];
+        sw[tid] = w;
+    }
     __syncthreads();
-    {                                          // delta_mu[c] = mu[c] - sum_j V[c][keep_j] w_j, kept columns split in two halves
+    {                                          // delta_mu[c] = mu[c] - sum_j V[c][keep_j] w_j, the kept columns in ranges
         float pr = 0.f;
-        const int j0 = half ? (r + 1) / 2 : 0, j1 = half ? r : (r + 1) / 2;
+        const int per = (r + EIGF_PARTS - 1) / EIGF_PARTS, j0 = min(pt * per, r), j1 = min(j0 + per, r);
         for (int j = j0; j < j1; ++j) pr = fmaf(Vs[x * EIGF_LD + skeep[j]], sw[j], pr);
-        part[half * D + x] = pr;
+        part[pt * D + x] = pr;
     }
     __syncthreads();
-    if (tid < D) dmu_out[(size_t)u * D + tid] = smu[tid] - (part[tid] + part[D + tid]);
+    if (tid < D) {
+        float pr = 0.f;
+#pragma unroll
+        for (int k = 0; k < EIGF_PARTS; ++k) pr += part[k * D + tid];
+        dmu_out[(size_t)u * D + tid] = smu[tid] - pr;
+    }
 }
 
 __global__ __launch_bounds__(256) void gather_rotation_kernel(int r, const float* __restrict__ R,
@@ -1301,7 +1322,7 @@ hipError_t launch_eig(int U, const float* cov, const float* sigma, const float* 
     }
     e = allow_dynamic_lds((const void*)eig_finish, EIGF_LDS_BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(eig_finish, dim3(U), dim3(256), EIGF_LDS_BYTES, st, r, R, keep_idx, mu, Rr, dmu);
+    hipLaunchKernelGGL(eig_finish, dim3(U), dim3(EIGF_THREADS), EIGF_LDS_BYTES, st, r, R, keep_idx, mu, Rr, dmu);
     return hipGetLastError();
 }
 
