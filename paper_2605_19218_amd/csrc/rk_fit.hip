@@ -651,7 +651,7 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
         float tn;
         jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
         prm[lk] = make_float2(ps, ptau);
-        if (!WITH_V) rot_u[lk] = make_float2(ps, ptau);
+        if (!WITH_V) rot_u[lk] = lk == 0 ? make_float2(-ps, -ptau) : make_float2(ps, ptau);   // pair 0: see eig_apply_rotations
         dOff = (ps == 0.f) ? apq : 0.f;                    // left as it is when the rotation is skipped
         dE00 = app - tn * apq;
         dE11 = aqq + tn * apq;
@@ -664,8 +664,9 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
     if (WITH_V) {
 #pragma unroll
         for (int i = 0; i < EIGV_FUSED_ROWS; ++i) {
-            vtop[i] = (wave > 0 && vrow0 + i == 2 * lane) ? 1.f : 0.f;
-            vbot[i] = (wave > 0 && vrow0 + i == 2 * lane + 1) ? 1.f : 0.f;
+            // lane 0 holds its pair exchanged (position 1 on top): see eig_apply_rotations
+            vtop[i] = (wave > 0 && vrow0 + i == (lane == 0 ? 1 : 2 * lane)) ? 1.f : 0.f;
+            vbot[i] = (wave > 0 && vrow0 + i == (lane == 0 ? 0 : 2 * lane + 1)) ? 1.f : 0.f;
         }
     }
 
@@ -700,13 +701,17 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
             float tn;
             jacobi_params(app, aqq, apq, thr_skip, ps, ptau, tn);
             pnext[lk] = make_float2(ps, ptau);
-            if (!WITH_V && t + 1 < EIG_ROT_ROUNDS) rot_u[(size_t)(t + 1) * 64 + lk] = make_float2(ps, ptau);
+            if (!WITH_V && t + 1 < EIG_ROT_ROUNDS)
+                rot_u[(size_t)(t + 1) * 64 + lk] = lk == 0 ? make_float2(-ps, -ptau) : make_float2(ps, ptau);
             dOff = (ps == 0.f) ? apq : 0.f;
             dE00 = app - tn * apq;
             dE11 = aqq + tn * apq;
         }
         float2 pv = make_float2(0.f, 0.f);
-        if (WITH_V && wave != 0) pv = pcur[lane];
+        if (WITH_V && wave != 0) {
+            pv = pcur[lane];
+            if (lane == 0) pv = make_float2(-pv.x, -pv.y);
+        }
         float a[2][4];
         float2 p1[2], p2[2];
 #pragma unroll
@@ -731,14 +736,14 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
             if (act[ts]) { nxt[wa[ts][0]] = xa0; nxt[wb[ts][0]] = xb0; nxt[wa[ts][1]] = xa1; nxt[wb[ts][1]] = xb1; }
         }
         if (WITH_V && wave != 0) {                      // V <- V J, then the columns move (see eig_apply_rotations)
-            const bool lane1 = lane == 1;
+            const bool lane0 = lane == 0;
 #pragma unroll
             for (int i = 0; i < EIGV_FUSED_ROWS; ++i) {
                 const float x = vtop[i], y = vbot[i];
                 const float xn = x - pv.x * (y + pv.y * x), yn = y + pv.x * (x - pv.y * y);
-                const float t_up = lane_from_below(xn, xn), b_up = lane_from_below(yn, yn);
-                vtop[i] = lane1 ? b_up : t_up;
-                vbot[i] = lane_from_above(xn, yn);
+                const float b_dn = lane_from_above(xn, yn);
+                vtop[i] = lane_from_below(b_dn, xn);
+                vbot[i] = lane0 ? yn : b_dn;
             }
         }
         __syncthreads();
@@ -787,7 +792,8 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
 #pragma unroll
         for (int i = 0; i < EIGV_FUSED_ROWS; ++i)
             if (vrow0 + i < D)
-                *(float2*)(R_out + (size_t)u * D * D + (size_t)(vrow0 + i) * D + 2 * lane) = make_float2(vtop[i], vbot[i]);
+                *(float2*)(R_out + (size_t)u * D * D + (size_t)(vrow0 + i) * D + 2 * lane) =
+                    lane == 0 ? make_float2(vbot[i], vtop[i]) : make_float2(vtop[i], vbot[i]);
     }
     __syncthreads();
     if (tid < D) {
@@ -804,11 +810,15 @@ __global__ __launch_bounds__(EIG_THREADS) void eig_jacobi_rotations(const float*
 }
 
 // V <- V J_1 J_2 ... over the recorded rounds, V = I at the start.  Wave = four rows of V; lane k
-// holds the elements at positions 2 k ("top") and 2 k + 1 ("bottom") of each row.  A round rotates
-// every lane's pair and then moves the columns to their next positions, which for this layout is a
-// shift of the tops by one lane upwards and of the bottoms by one lane downwards across the whole
-// wave (data-parallel-primitive moves, no LDS): lane 0 keeps its top, lane 1 takes lane 0's bottom
-// as its top, lane 63 takes its own top as its bottom.  Grid (8, U), 256 threads.
+// holds the elements at positions 2 k ("top") and 2 k + 1 ("bottom") of each row -- except lane 0,
+// which holds its pair exchanged (position 1 on top, the position 0 that never moves at the bottom;
+// its recorded rotation is stored negated, which is the same rotation with the two roles swapped).
+// A round rotates every lane's pair and then moves the columns to their next positions.  With lane 0
+// exchanged the 127 moving positions form one ring through the registers: up the tops from lane 0 to
+// lane 63, down the bottoms from lane 63 to lane 1, and back into lane 0's top.  That is two whole-wave
+// shifts by one lane (data-parallel-primitive moves, no LDS) -- the bottoms move down, lane 63 taking
+// its own top; the tops move up, lane 0 taking what came down to it -- and one select that puts the
+// fixed element back: 7 vector instructions per row and round.  Grid (8, U), 256 threads.
 constexpr int EIGV_ROWS = 4;
 __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restrict__ rot,
                                                            const int32_t* __restrict__ sweeps_ws,
@@ -822,18 +832,18 @@ __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restr
     float top[EIGV_ROWS], bot[EIGV_ROWS];
 #pragma unroll
     for (int i = 0; i < EIGV_ROWS; ++i) {
-        top[i] = (row0 + i == 2 * lane) ? 1.f : 0.f;
-        bot[i] = (row0 + i == 2 * lane + 1) ? 1.f : 0.f;
+        top[i] = (row0 + i == (lane == 0 ? 1 : 2 * lane)) ? 1.f : 0.f;
+        bot[i] = (row0 + i == (lane == 0 ? 0 : 2 * lane + 1)) ? 1.f : 0.f;
     }
-    const bool lane1 = lane == 1;
+    const bool lane0 = lane == 0;
     auto apply = [&](float2 p) {
 #pragma unroll
         for (int i = 0; i < EIGV_ROWS; ++i) {
             const float x = top[i], y = bot[i];
             const float xn = x - p.x * (y + p.y * x), yn = y + p.x * (x - p.y * y);
-            const float t_up = lane_from_below(xn, xn), b_up = lane_from_below(yn, yn);
-            top[i] = lane1 ? b_up : t_up;
-            bot[i] = lane_from_above(xn, yn);
+            const float b_dn = lane_from_above(xn, yn);      // lane k <- bottom of lane k + 1; lane 63 <- its own top
+            top[i] = lane_from_below(b_dn, xn);              // lane k <- top of lane k - 1; lane 0 <- what came down to it
+            bot[i] = lane0 ? yn : b_dn;                      // position 0 stays
         }
     };
     constexpr int PF = 8;                                  // rounds of rotations requested ahead
@@ -857,7 +867,8 @@ __global__ __launch_bounds__(256) void eig_apply_rotations(const float2* __restr
     for (; t < n_rounds; ++t) apply(rot_u[(size_t)t * 64]);
 #pragma unroll
     for (int i = 0; i < EIGV_ROWS; ++i)
-        *(float2*)(R_out + (size_t)u * D * D + (size_t)(row0 + i) * D + 2 * lane) = make_float2(top[i], bot[i]);
+        *(float2*)(R_out + (size_t)u * D * D + (size_t)(row0 + i) * D + 2 * lane) =
+            lane == 0 ? make_float2(bot[i], top[i]) : make_float2(top[i], bot[i]);
 }
 
 // R_r = R[:, keep] and delta_mu = mu - R_r R_r^T mu (Alg. 1 step 14 and 16), one work-group per matrix;
