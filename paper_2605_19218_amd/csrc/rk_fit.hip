@@ -1001,7 +1001,7 @@ hipError_t launch_cov_finalize(const RowsDev& rows, int B, int Hkv, int n_chunks
 //
 // One iteration:
 //   W <- diag(sigma) C diag(sigma) W   register-tiled: thread = 4 rows x RJ columns
-//                                      (columns 32 apart), C read from global/L2 as
+//                                      (adjacent pairs), C read from global/L2 as
 //                                      float4 broadcasts, in place via registers;
 //   G <- W^T W (lower, 2x2 blocks), rho = eps tr(G) / k added to the diagonal;
 //   right-looking elimination of the stacked matrix [W; G], one barrier per column,
@@ -1021,8 +1021,8 @@ __host__ __device__ inline int sub_row_stride(int k)
 }
 __host__ __device__ inline size_t sub_lds_bytes(int k)
 {
-    const size_t kpad = 16 * (size_t)((k + 15) / 16);
-    return sizeof(double) * ((size_t)D * sub_row_stride(k) + (size_t)k * (k + 1) / 2 + 2 * (size_t)(k + 4) + D + 2 * kpad);
+    const size_t kpad = 16 * (size_t)((k + 15) / 16) + 8;      // one published pivot row: 4 parts x (columns / 4 + 2)
+    return sizeof(double) * ((size_t)D * sub_row_stride(k) + (size_t)k * (k + 1) / 2 + 2 * (size_t)(k + 4) + D + 2 * kpad + 2);
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v)
@@ -1063,27 +1063,39 @@ __device__ __forceinline__ double quad_bcast(double v)
 // The code is straight-line per block of four steps; a pivot that is not positive is only
 // recorded, the remaining steps then run on meaningless numbers and the caller discards the
 // result (early exits here made the register allocator spill the whole row).
+// The published row is laid out by part: element (part, c) = column part + 4 c at rb[part * (NCOL + 2) + c],
+// so that a thread's columns are consecutive doubles and two of them come with one 16-byte LDS read
+// (the LDS pipeline issues about one wave-wide instruction per five cycles whatever its width, and a
+// step is little else than these reads); the stride NCOL + 2 keeps the four parts of a wave in
+// different banks and every even c 16-byte aligned.
 template <int NCOL, int CJ, int PJ>
 __device__ __forceinline__ void elim_step(double (&x)[NCOL], double* __restrict__ rb, double* __restrict__ piv,
                                           int row, int part, int tid, bool& bad)
 {
-    constexpr int j = 4 * CJ + PJ;
+    constexpr int j = 4 * CJ + PJ, RS = NCOL + 2;
+    double* rbp = rb + part * RS;
     if (row == D + j) {
         const double gjj = quad_bcast<PJ>(x[CJ]);
         const double rinv = fast_rcp_f64(gjj);
-        if (part == PJ) rb[j] = gjj;
-        else if (part > PJ) rb[4 * CJ + part] = x[CJ] * rinv;
+        if (part == PJ) rbp[CJ] = gjj;
+        else if (part > PJ) rbp[CJ] = x[CJ] * rinv;
 #pragma unroll
-        for (int c = CJ + 1; c < NCOL; ++c) rb[4 * c + part] = x[c] * rinv;
+        for (int c = CJ + 1; c < NCOL; ++c) rbp[c] = x[c] * rinv;
     }
     __syncthreads();
-    const double gjj = rb[j];
+    const double gjj = rb[PJ * RS + CJ];
     bad = bad || !(gjj > 0.0);
     if (tid == 0) piv[j] = gjj;
     const double f = -quad_bcast<PJ>(x[CJ]);
-    if (part > PJ) x[CJ] = fma(f, rb[4 * CJ + part], x[CJ]);
+    if (part > PJ) x[CJ] = fma(f, rbp[CJ], x[CJ]);
+    constexpr int c0 = CJ + 1, c1 = (c0 + 1) & ~1;          // c1: first even column index from c0 on
+    if constexpr ((c0 & 1) != 0 && c0 < NCOL) x[c0] = fma(f, rbp[c0], x[c0]);
 #pragma unroll
-    for (int c = CJ + 1; c < NCOL; ++c) x[c] = fma(f, rb[4 * c + part], x[c]);
+    for (int c = c1; c + 1 < NCOL; c += 2) {
+        const double2 v = *(const double2*)(rbp + c);
+        x[c] = fma(f, v.x, x[c]);
+        x[c + 1] = fma(f, v.y, x[c + 1]);
+    }
 }
 
 // Blocks CJ, CJ + 1, ... while they exist (4 CJ < kp4, uniform); nested so that the register
@@ -1119,9 +1131,10 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
     double* tv = piv + k + 4;                             // [k + 4]
     double* sig = tv + k + 4;                             // [D]
     double* rowbuf2 = sig + D;                            // [2][kpad]: the published pivot row, double-buffered
+    rowbuf2 += ((uintptr_t)rowbuf2 >> 3) & 1;             // 16-byte aligned (the packed triangle has k (k + 1) / 2 doubles)
     constexpr int RJ = (KB + 1) / 2;                      // GEMM columns per thread (32 apart)
     constexpr int NCOL = 4 * KB;                          // elimination: columns per thread (4 apart)
-    const int kpad = 4 * NCOL;
+    const int kpad = 4 * (NCOL + 2);                      // one published row: [part][NCOL + 2]
 
     const int u = blockIdx.x, tid0 = threadIdx.x, tid = tid0;
     const float* C = cov + (size_t)u * D * D;
@@ -1145,7 +1158,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         // phases, and spilled.
         int tid = tid0;
         asm volatile("" : "+v"(tid));
-        int ib = tid >> 5, jb = tid & 31;                  // GEMM tile: rows 4 ib .. +3, columns jb + 32 c
+        int ib = tid >> 5, jb = tid & 31;                  // GEMM tile: rows 4 ib .. +3, columns gemm_col(c)
         // ---- W <- C_q W ----
         if (weighted) {
             for (int idx = tid; idx < D * k; idx += SUB_THREADS) {
@@ -1159,9 +1172,10 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int c = 0; c < RJ; ++c) acc[r][c] = 0.0;
-        int col[RJ];
-#pragma unroll
-        for (int c = 0; c < RJ; ++c) col[c] = min(jb + 32 * c, k - 1);     // clamped: surplus lanes recompute a real column
+        // a thread's columns come in adjacent pairs, 64 c' + 2 jb and + 1 (c' = 0 .. RJ / 2 - 1), so that a pair is
+        // one 16-byte LDS read, plus the single column 64 (RJ / 2) + jb when RJ is odd; reads of surplus threads
+        // are clamped onto the end of the padded row, and they store nothing
+        auto gemm_col = [&](int c) { return c < (RJ & ~1) ? 64 * (c >> 1) + 2 * jb + (c & 1) : 64 * (RJ >> 1) + jb; };
 #pragma unroll 2
         for (int m0 = 0; m0 < D; m0 += 4) {          // bounded unroll: a full unroll hoists 512 registers of C
             float4 c4[4];
@@ -1170,8 +1184,14 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
 #pragma unroll
             for (int mm = 0; mm < 4; ++mm) {
                 double wv[RJ];
+                const double* wrow = W + (m0 + mm) * ks;
 #pragma unroll
-                for (int c = 0; c < RJ; ++c) wv[c] = W[(m0 + mm) * ks + col[c]];
+                for (int c = 0; c + 1 < RJ; c += 2) {
+                    const double2 w2 = *(const double2*)(wrow + min(gemm_col(c), (ks - 2) & ~1));
+                    wv[c] = w2.x;
+                    wv[c + 1] = w2.y;
+                }
+                if (RJ & 1) wv[RJ - 1] = wrow[min(gemm_col(RJ - 1), ks - 1)];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float cf = mm == 0 ? c4[r].x : mm == 1 ? c4[r].y : mm == 2 ? c4[r].z : c4[r].w;
@@ -1186,7 +1206,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int c = 0; c < RJ; ++c)
-                if (jb + 32 * c < k) W[(4 * ib + r) * ks + jb + 32 * c] = acc[r][c] * sig[4 * ib + r];
+                if (gemm_col(c) < k) W[(4 * ib + r) * ks + gemm_col(c)] = acc[r][c] * sig[4 * ib + r];
         __syncthreads();
 
         // ---- G <- W^T W (lower triangle, 2 x 2 blocks) ----

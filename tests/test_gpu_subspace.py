@@ -51,6 +51,9 @@ CASES = [
     ("bf16_k96_uncentered", "bf16", 1, 2, 600, None, 96, 5, 1e-6, False, False),
     ("bf16_k104_max", "bf16", 1, 1, 400, None, 104, 3, 1e-5, False, True),
     ("bf16_k37_odd", "bf16", 1, 2, 400, None, 37, 5, 1e-6, True, True),
+    # k = 72 leaves no padding columns in the basis's LDS rows, k = 80 gives a thread an odd number of columns
+    ("bf16_k72_unpadded", "bf16", 1, 2, 500, None, 72, 5, 1e-6, True, True),
+    ("bf16_k80", "bf16", 2, 1, 700, [700, 333], 80, 5, 1e-6, False, True),
     ("bf16_k8_T1", "bf16", 1, 1, 300, None, 8, 1, 0.0, False, True),
     ("bf16_k1", "bf16", 1, 1, 300, None, 1, 4, 1e-6, False, True),
 ]
