@@ -1083,6 +1083,10 @@ __device__ __forceinline__ void elim_step(double (&x)[NCOL], double* __restrict_
         for (int c = CJ + 1; c < NCOL; ++c) rbp[c] = x[c] * rinv;
     }
     __syncthreads();
+    // The wave that holds stack row 128 + j + 1 publishes next: its reads, its update and the reciprocal are the
+    // dependent chain between this barrier and the next one, so it issues ahead of the others.
+    if (__builtin_amdgcn_readfirstlane(tid >> 6) == ((D + j + 1) >> 4)) __builtin_amdgcn_s_setprio(3);
+    else __builtin_amdgcn_s_setprio(0);
     const double gjj = rb[PJ * RS + CJ];
     bad = bad || !(gjj > 0.0);
     if (tid == 0) piv[j] = gjj;
@@ -1264,6 +1268,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
             }
             bool bad = false;
             elim_block<NCOL, 0>(x, rowbuf2, piv, kp4, kpad, row, part, tid, bad);
+            __builtin_amdgcn_s_setprio(0);
             if (bad) { fail = t + 1; break; }              // uniform: every thread saw the same pivots
             __syncthreads();                               // piv complete
             if (tid < k) tv[tid] = 1.0 / sqrt(piv[tid]);
