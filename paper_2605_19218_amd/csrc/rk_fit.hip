@@ -1047,6 +1047,10 @@ __device__ __forceinline__ double fast_rcp_f64(double g)
     return fma(r, e, r);
 }
 
+// Two doubles as one 16-byte LDS access: a true vector type keeps the access whole (the struct double2 is loaded
+// member by member, and the pair then comes back as a two-address 8-byte read, which takes almost twice as long).
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
 // value of lane (quad base + PJ) for every lane of the quad
 template <int PJ>
 __device__ __forceinline__ double quad_bcast(double v)
@@ -1100,7 +1104,7 @@ __device__ __forceinline__ void elim_step(double (&x)[NCOL], double* __restrict_
     if constexpr ((c0 & 1) != 0 && c0 < NCOL) x[c0] = fma(f, rbp[c0], x[c0]);
 #pragma unroll
     for (int c = c1; c + 1 < NCOL; c += 2) {
-        const double2 v = *(const double2*)(rbp + c);
+        const f64x2 v = *(const f64x2*)(rbp + c);
         x[c] = fma(f, v.x, x[c]);
         x[c + 1] = fma(f, v.y, x[c + 1]);
     }
@@ -1195,7 +1199,7 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
                 const double* wrow = W + (m0 + mm) * ks;
 #pragma unroll
                 for (int c = 0; c + 1 < RJ; c += 2) {
-                    const double2 w2 = *(const double2*)(wrow + min(gemm_col(c), (ks - 2) & ~1));
+                    const f64x2 w2 = *(const f64x2*)(wrow + min(gemm_col(c), (ks - 2) & ~1));
                     wv[c] = w2.x;
                     wv[c + 1] = w2.y;
                 }
@@ -1226,8 +1230,8 @@ __global__ __launch_bounds__(SUB_THREADS) void subspace_iter(const float* __rest
             const int pb = blk - pa * (pa + 1) / 2;
             double s00 = 0.0, s01 = 0.0, s10 = 0.0, s11 = 0.0;
             for (int i = 0; i < D; ++i) {
-                const double2 wa = *(const double2*)(W + i * ks + 2 * pa);
-                const double2 wb = *(const double2*)(W + i * ks + 2 * pb);
+                const f64x2 wa = *(const f64x2*)(W + i * ks + 2 * pa);
+                const f64x2 wb = *(const f64x2*)(W + i * ks + 2 * pb);
                 s00 = fma(wa.x, wb.x, s00);
                 s01 = fma(wa.x, wb.y, s01);
                 s10 = fma(wa.y, wb.x, s10);
