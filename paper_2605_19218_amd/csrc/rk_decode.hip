@@ -608,6 +608,16 @@ __device__ __forceinline__ void load_tile(DecTile<R>& T, const bf16_t* __restric
     load_tile_v<R>(T, Vu, tok0, lane);
 }
 
+// A float that another work-group of this launch wrote, read past this compute unit's L1 (agent-scope load).
+// The (m, l) rows and the appended token's scores are a few bytes per head, so one cache line holds those of
+// several units; a compute unit that folded one of them earlier in the launch may still hold that line as it
+// was then, and a plain load would hit it.  The accumulator rows are 512 bytes per partial and are read by
+// nobody but the unit's own fold, so they come through plain 16-byte loads.
+__device__ __forceinline__ float load_past_l1(const float* p)
+{
+    return __hip_atomic_load(const_cast<float*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Fold of S partials (m, l, acc) for one (row, 8 channels) in ascending order, MC at a time: every
 // load of a chunk is issued before the first use, so a chunk costs one round trip to the L2.
 template <int MC>
@@ -622,8 +632,9 @@ __device__ __forceinline__ void fold_partials(const float* pm, const float* pl, 
             const int i = min(i0 + k, S - 1);
             a0[k] = *(const f32x4*)(pa + (size_t)i * D);
             a1[k] = *(const f32x4*)(pa + (size_t)i * D + 4);
-            mv[k] = i0 + k < S ? pm[i] : NEG_INF;
-            lv[k] = pl[i];
+            const float mi = load_past_l1(pm + i);
+            mv[k] = i0 + k < S ? mi : NEG_INF;
+            lv[k] = load_past_l1(pl + i);
         }
         float Mc = M;
 #pragma unroll
@@ -650,9 +661,9 @@ __device__ __forceinline__ void fold_partials(const float* pm, const float* pl, 
 // Vector stores stay counted until the L2 has acknowledged them, so after the wait and the barrier
 // every partial of this work-group is in the XCD's L2, and the counter increment that follows is
 // ordered behind them.  All work-groups of a unit run on one XCD (see the index mapping in the
-// kernel), so the one that draws the last ticket finds all partials in that same L2; it has never
-// read those lines before, so its L1 holds nothing stale.  The fold runs in slot order, whoever
-// does it.  `bump`: this launch also appends a row (rotated cache: NEW = true, the row's own score in
+// kernel), so the one that draws the last ticket finds all partials in that same L2; what its own
+// L1 may hold of them from an earlier fold on the same compute unit it reads around (load_past_l1).
+// The fold runs in slot order, whoever does it.  `bump`: this launch also appends a row (rotated cache: NEW = true, the row's own score in
 // snew and its Values in v_new enter as one more term; text segment: NEW = false, the text
 // work-groups already counted it); the length of batch item b moves once every work-group of the
 // item -- they sit on different XCDs, hence a second, device-wide set of tickets -- has taken one,
@@ -689,7 +700,7 @@ __device__ __forceinline__ void fold_unit(int unit, int unit_parts, int n_slots,
         float sx = NEG_INF;
         uint4 vraw = make_uint4(0, 0, 0, 0);
         if (NEW && snew) {                                   // the appended token: one more term of the softmax
-            sx = snew[row];
+            sx = load_past_l1(snew + row);
             vraw = *(const uint4*)(v_new + (size_t)u * D + c0);
         }
         if (n_slots <= 8) fold_partials<8>(pm, pl, pa, n_slots, M, den, n0, n1);     // one round trip to the L2

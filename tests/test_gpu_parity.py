@@ -339,6 +339,9 @@ DECODE_CASES = [
     ("merge_in_split_mha_r96", "bf16", 1, 8, 8, 4096, None, 96, False, 0),
     ("merge_in_split_s20", "bf16", 2, 28, 4, 2600, [2600, 2047], 37, False, 20),
     ("merge_in_split_g20", "bf16", 4, 20, 1, 1500, [1500, 640, 3, 1279], 32, False, 3),
+    # one head per unit and two splits: the (m, l) partials of sixteen units share one 128-byte line, and
+    # several times more work-groups than the device holds at once, so a compute unit folds one unit after another
+    ("merge_in_split_mha_many_units", "bf16", 24, 32, 32, 700, None, 32, False, 2),
 ]
 
 
