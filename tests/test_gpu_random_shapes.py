@@ -24,12 +24,14 @@ def ctx():
     rk.rk_destroy(c)
 
 
-def draw(seed):
+def draw(seed, wide=False):
+    """wide: many (batch item, KV head) units and short caches, so that each XCD serves several units, a
+    compute unit several work-groups in turn, and the folded merge its two- and three-split forms."""
     g = np.random.Generator(np.random.Philox(key=9000 + seed))
-    B = int(g.integers(1, 4))
-    Hkv = int(g.choice([1, 2, 4]))
-    G = int(g.choice([1, 2, 4, 7, 8, 15, 16, 20]))
-    L = int(g.choice([1, 31, 33, 127, 129, 500, 1023, 1500, 2100]))
+    B = int(g.integers(4, 13)) if wide else int(g.integers(1, 4))
+    Hkv = int(g.choice([8, 16, 32])) if wide else int(g.choice([1, 2, 4]))
+    G = int(g.choice([1, 1, 2, 4])) if wide else int(g.choice([1, 2, 4, 7, 8, 15, 16, 20]))
+    L = int(g.choice([97, 160, 300, 700])) if wide else int(g.choice([1, 31, 33, 127, 129, 500, 1023, 1500, 2100]))
     lengths = [int(g.integers(0, L + 1)) for _ in range(B)]
     lengths[int(g.integers(0, B))] = L                       # one sequence is full
     r = int(g.integers(1, 129))
@@ -40,9 +42,9 @@ def draw(seed):
     return B, Hkv, G, L, lengths, r, dtype, splits, cap_t, lens_t
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", list(range(16)) + [100 + i for i in range(6)])
 def test_random_shape(ctx, seed):
-    B, Hkv, G, L, lengths, r, dtype, splits, cap_t, lens_t = draw(seed)
+    B, Hkv, G, L, lengths, r, dtype, splits, cap_t, lens_t = draw(seed, wide=seed >= 100)
     Hq = Hkv * G
     data = layer(B, Hq, Hkv, L, dtype, 70 + seed, lengths=lengths, mean_shift=1.0)
     p = run_prefill(ctx, data, B, Hq, Hkv, L, r, dtype, lengths=lengths, cap=L + 3)
