@@ -11,8 +11,10 @@ in HBM.
 
 Prints ONE JSON line.
   value      decode-attention achieved HBM bandwidth INSIDE the step: algorithmic bytes
-             B*H_kv*L*(r+d)*2 / HIP-event time of the rk_decode_attn call (launch latency
-             after the preceding call included).
+             B*H_kv*L*(r+d)*2 / HIP-event time of the rk_decode_attn call in a second,
+             instrumented pass of K steps (the event in front of the call costs the device
+             5-6 idle microseconds, which this figure includes; ms_per_step comes from the
+             first pass, which records nothing between its calls).
   roofline   the decode kernel itself: the same bytes / launch duration, HIP events around N
              back-to-back launches on the launch stream (what rocprofv3 --kernel-trace
              reports per launch), against the 8 TB/s datasheet peak and against the
@@ -184,14 +186,22 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(args.steps)]
+    # The timed region: K steps and nothing else.  An event recorded between two calls drains the device and the
+    # kernel behind it starts 5-6 us later (rocprofv3 shows that idle gap after every record and none between
+    # kernels of consecutive calls), so the per-stage events run in a second pass of K steps of their own.
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, evs[i])
+        step(args.warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        step(args.warmup + args.steps + i, evs[i])
+    torch.cuda.synchronize()
 
     stage_us = {}
     for s, (name, _) in enumerate(STAGES):
@@ -585,7 +595,9 @@ def main():
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "L": L, "keep": r_main,
                    "ring_layers": NL, "decode_splits": n_splits, "tokens_per_split": tps},
         "us_per_decode_step": dec_us,
-        "value_note": "HIP-event time of the rk_decode_attn call inside the step (launch latency behind the append included)",
+        "value_note": "HIP-event time of the rk_decode_attn call inside an instrumented step: it includes the 5-6 us the "
+                      "device idles after the event recorded in front of the call; the kernel itself takes the same time "
+                      "there as back to back (roofline.duration_us; profiles/kernel_trace_step_C3.md)",
         "stages_us": stage_us,
         "roofline": {"bound": "hbm", "achieved": main_b2b["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": main_b2b["frac_of_peak"], "traffic": committed_traffic("decode_split_mfma<64>"),
