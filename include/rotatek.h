@@ -31,7 +31,10 @@
  *   - Cache layout: the packed rotated keys K~ and the values V live in two
  *     caller-allocated buffers of rk_cache_bytes() bytes whose INTERNAL layout is
  *     fragment-major (tiled so that the decode kernel's matrix-core operands are
- *     contiguous 1 KB pieces of HBM): per (b, h_kv) slab of `capacity` tokens,
+ *     contiguous 1 KB pieces of HBM): per (b, h_kv) slab of `capacity` tokens
+ *     (from 4096 tokens on, consecutive slabs are spaced up to 255 tokens further
+ *     apart than `capacity`, which keeps the decode's concurrent streams on
+ *     different memory channels; rk_cache_bytes() includes that spacing),
  *       K~ element (token t, channel c):  [t/16][c/8][t%16][c%8], keep padded to 16
  *       V  element (token t, channel c):  [t/32][c/16][g][c%16][jj],
  *                                         g = (t%16)/4, jj = 4*((t%32)/16) + t%4

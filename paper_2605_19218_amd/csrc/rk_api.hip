@@ -321,7 +321,7 @@ rk_status rk_cache_bytes(const rk_layout* L, size_t* k_packed_bytes, size_t* v_c
 {
     rk_status s = check_layout(nullptr, L);
     if (s != RK_OK) return s;
-    const size_t slabs = (size_t)L->batch * L->n_kv_heads * L->capacity;
+    const size_t slabs = (size_t)L->batch * L->n_kv_heads * slab_tokens(L->capacity);       // slabs are spaced, see slab_tokens()
     if (k_packed_bytes) *k_packed_bytes = slabs * keep_padded(L->keep) * elem_size(L->dtype);
     if (v_cache_bytes) *v_cache_bytes = slabs * D * elem_size(L->dtype);
     return RK_OK;

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void compress_generic(RowsDev rows, int Hkv, i
     }
     __syncthreads();
     const float* Ru = Rr + (size_t)u * D * r;
-    T* Ku = Kp + (size_t)u * cap * rp;
+    T* Ku = Kp + (size_t)u * slab_tokens(cap) * rp;
     for (int o = tid; o < nt * rp; o += 256) {
         int t = o / rp, j = o - t * rp;
         float a = 0.f;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256, 2) void compress_mfma(RowsDev rows, int Hkv, i
     const bf16_t* base = (const bf16_t*)rows.data;
     const int64_t hb = (int64_t)b * rows.sb + (int64_t)h * rows.sh;
     const int32_t* list = GATHER ? rows.tok_idx + rows.tok_off[b] : nullptr;
-    bf16_t* Ku = Kp + (size_t)u * cap * R;
+    bf16_t* Ku = Kp + (size_t)u * slab_tokens(cap) * R;
 
     // Row numbers of one pass of this wave (token list entries; the token itself without a list).
     // Rows past the end are clamped to the last row (never stored).
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void v_retile(RowsDev rows, int Hkv, int cap, 
         tile[row][oc] = x;
     }
     __syncthreads();
-    T* Vu = dst + (size_t)u * cap * D + (size_t)blockIdx.x * 4096;
+    T* Vu = dst + (size_t)u * slab_tokens(cap) * D + (size_t)blockIdx.x * 4096;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         int o = tid + 256 * k;                   // piece index: [cb][g][n]
@@ -356,9 +356,9 @@ __global__ __launch_bounds__(256) void append_rows(int Hkv, int cap, int r, cons
             if (act) part[cq][j] = a;
         }
         __syncthreads();
-        if (tid < rp) st_elem(Kp + (size_t)u * cap * rp + kidx(len, tid, rp),        // zeros in the padding
+        if (tid < rp) st_elem(Kp + (size_t)u * slab_tokens(cap) * rp + kidx(len, tid, rp),        // zeros in the padding
                               tid < r ? (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]) : 0.f);
-        if (tid < D) Vc[(size_t)u * cap * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
+        if (tid < D) Vc[(size_t)u * slab_tokens(cap) * D + vidx(len, tid)] = v_new[(size_t)u * D + tid];
     }
     __syncthreads();
     if (tid == 0) {
@@ -383,13 +383,13 @@ __global__ __launch_bounds__(256) void unpack_cache(int cap, int r, const T* __r
     if (k_rows) {
         for (int idx = threadIdx.x; idx < 32 * r; idx += 256) {
             int t = t0 + idx / r, j = idx % r;
-            if (t < cap) k_rows[((size_t)u * cap + t) * r + j] = Kp[(size_t)u * cap * rp + kidx(t, j, rp)];
+            if (t < cap) k_rows[((size_t)u * cap + t) * r + j] = Kp[(size_t)u * slab_tokens(cap) * rp + kidx(t, j, rp)];
         }
     }
     if (v_rows) {
         for (int idx = threadIdx.x; idx < 32 * D; idx += 256) {
             int t = t0 + (idx >> 7), c = idx & 127;
-            if (t < cap) v_rows[((size_t)u * cap + t) * D + c] = Vc[(size_t)u * cap * D + vidx(t, c)];
+            if (t < cap) v_rows[((size_t)u * cap + t) * D + c] = Vc[(size_t)u * slab_tokens(cap) * D + vidx(t, c)];
         }
     }
 }

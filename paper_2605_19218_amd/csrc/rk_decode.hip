@@ -88,8 +88,8 @@ __global__ __launch_bounds__(128) void decode_split_generic(
 
     float m = NEG_INF, l = 0.f, acc = 0.f;
     const int rp = keep_padded(r);
-    const T* Ku = Kp + (size_t)u * cap * rp;
-    const T* Vu = Vc + (size_t)u * cap * D;
+    const T* Ku = Kp + (size_t)u * slab_tokens(cap) * rp;
+    const T* Vu = Vc + (size_t)u * slab_tokens(cap) * D;
     for (int base = t0; base < t1; base += 128) {
         const int tok = base + tid;
         const bool valid = tok < t1;
@@ -945,8 +945,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
     const int tp = tiles_all / S, trem = tiles_all - tp * S;
     const int t0 = 128 * (split * tp + max(split - (S - trem), 0));
     const int t1_full = 128 * ((split + 1) * tp + max(split + 1 - (S - trem), 0));
-    const bf16_t* Ku = Kp + (size_t)u * cap * R;
-    const bf16_t* Vu = Vc + (size_t)u * cap * D;
+    const bf16_t* Ku = Kp + (size_t)u * slab_tokens(cap) * R;
+    const bf16_t* Vu = Vc + (size_t)u * slab_tokens(cap) * D;
 
     // prologue operands, in matrix-core layout (lane (g, n)):
     //   qfrag[i]     B operand: q of head n, channels 32 i + 8 g ..+7 (q is bf16: exact);
@@ -1091,10 +1091,10 @@ __global__ __launch_bounds__(256, 2) void decode_split_mfma(
         } else if (app_here && app_ok && grp == 0) {
             if (wave == 1) {
                 for (int j = lane; j < R; j += 64)
-                    Kp[(size_t)u * cap * R + kidx(seq_raw, j, R)] = f32_to_bf16(qt[15][j]);
+                    Kp[(size_t)u * slab_tokens(cap) * R + kidx(seq_raw, j, R)] = f32_to_bf16(qt[15][j]);
             } else {
                 const int c = tid - 128;
-                Vc[(size_t)u * cap * D + vidx(seq_raw, c)] = v_new[(size_t)u * D + c];
+                Vc[(size_t)u * slab_tokens(cap) * D + vidx(seq_raw, c)] = v_new[(size_t)u * D + c];
             }
         }
 

@@ -92,6 +92,16 @@ __device__ __forceinline__ int64_t row_off(int64_t head_base, int64_t st, const 
 //    P.V MFMA as produced and lane (g, n) reads V's B-fragment for channel block
 //    cb as one 16-byte piece.
 __host__ __device__ __forceinline__ int keep_padded(int r) { return (r + 15) & ~15; }
+// Tokens from one (batch item, KV head) slab to the next inside either cache.  Every work-group of a decode
+// launch streams its own contiguous piece of some slab, all at the same pace, so the distance between the slabs
+// decides which memory channels the pieces share at any moment: with the slabs `capacity` tokens apart a
+// capacity of 16384 + 128 took 45 us per decode step where 16384 + 64 took 36.5 us (+ 96 and + 160: 39-40 us).
+// Larger caches therefore space their slabs at the next count that is 64 above a multiple of 256 tokens (at
+// most 255 tokens, i.e. at most 6 %, of padding per slab); rk_cache_bytes() includes it.
+__host__ __device__ __forceinline__ size_t slab_tokens(int cap)
+{
+    return cap < 4096 ? (size_t)cap : (size_t)((cap - 64 + 255) / 256) * 256 + 64;
+}
 __host__ __device__ __forceinline__ size_t kidx(int t, int c, int rp) {
     return (size_t)(t >> 4) * (16 * (size_t)rp) + (size_t)(c >> 3) * 128 + (size_t)(t & 15) * 8 + (c & 7);
 }

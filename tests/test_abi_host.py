@@ -125,6 +125,9 @@ def test_compress_append_validation(ctx):
     # cache sizes: keep is padded to a multiple of 16 channels
     assert rk.rk_cache_bytes(lay) == (2 * 2 * 1024 * 64 * 2, 2 * 2 * 1024 * 128 * 2)
     assert rk.rk_cache_bytes(layout(keep=37, dtype=rk.RK_F32))[0] == 2 * 2 * 1024 * 48 * 4
+    # from 4096 tokens on the slabs are spaced 64 tokens above a multiple of 256 (never closer than the capacity)
+    for cap, spaced in ((4064, 4064), (4096, 4160), (16384, 16448), (16448, 16448), (16480, 16704), (16512, 16704)):
+        assert rk.rk_cache_bytes(layout(capacity=cap)) == (2 * 2 * spaced * 64 * 2, 2 * 2 * spaced * 128 * 2), cap
 
 
 def test_decode_plan_and_options(ctx):
