@@ -444,7 +444,7 @@ def main():
             return torch.randn(*shape, generator=gen, **f32).to(torch.bfloat16)
 
         def run_workload(name, Bw, Hqw, Hkvw, Lw, r, rho, n_layers, lengths=None, n_text=0, keep_frac=1.0,
-                         decode_steps=0, reps=8):
+                         decode_steps=0, reps=8, text_rows=0):
             """fit, compress and decode of one configuration over a ring of n_layers layers."""
             out = dict(batch=Bw, n_q_heads=Hqw, n_kv_heads=Hkvw, L=Lw, keep=r, ring_layers=n_layers)
             tok_idx = tok_off = None
@@ -496,6 +496,20 @@ def main():
             out["decode"]["frac_of_stream_ceiling"] = out["decode"]["GBps"] / ceil_gbps
             out["decode_plan"] = dict(zip(("n_splits", "tokens_per_split"), rk.rk_decode_plan(ctx, layf(ring[0], n_max))))
             assert torch.isfinite(ring[0]["st"].out.float()).all(), name
+            if text_rows:
+                # Alg. 2 in full: the same rotated cache plus a full-width text segment of text_rows rows per KV head
+                text = rk.Text(synth_normal(Bw, Hkvw, text_rows, D), synth_normal(Bw, Hkvw, text_rows, D), text_rows,
+                               torch.full((Bw,), text_rows, device=dev, dtype=torch.int32), capacity=text_rows)
+
+                def decode_dual(i):
+                    ly = ring[i % n_layers]
+                    rk.rk_decode_attn_dual(ctx, layf(ly, n_max), ly["q"], ly["st"].Kp, ly["st"].Vc, ly["st"].Rr,
+                                           ly["st"].dmu, text, 0.0, ly["st"].out, wsd)
+                out["decode_dual"] = rate(tokens * Hkvw * (r + D) * 2 + Bw * Hkvw * text_rows * 2 * D * 2,
+                                          timed(decode_dual, 4 * reps, warm=n_layers))
+                out["decode_dual"]["text_rows"] = text_rows
+                assert torch.isfinite(ring[0]["st"].out.float()).all(), name
+                del text
             if decode_steps:
                 # the decode loop with the frozen rotation: every step appends one token to every layer of the ring
                 def loop_us(fused):
@@ -529,6 +543,9 @@ def main():
         c2, c4, c5 = CONFIGS["C2"], CONFIGS["C4"], CONFIGS["C5"]
         workloads = {}
         workloads["C2"] = run_workload("C2", c2["batch"], c2["n_q_heads"], c2["n_kv_heads"], c2["L"], c2["keep"], 16, 8, reps=16)
+        # the same layer as the paper splits it: 2880 image tokens in the rotated cache, 64 prompt tokens full-width
+        workloads["C2_dual"] = run_workload("C2_dual", c2["batch"], c2["n_q_heads"], c2["n_kv_heads"], c2["L"] - 64, c2["keep"],
+                                            16, 8, reps=16, text_rows=64)
         workloads["C2"]["note"] = "LLaVA-NeXT-7B-shaped layer: one decode step is 36 MB, a launch-latency regime"
         lengths = ragged_lengths(c4["id"], c4["batch"], *c4["ragged"])
         workloads["C4"] = run_workload("C4", c4["batch"], c4["n_q_heads"], c4["n_kv_heads"], int(lengths.max()), c4["keep"], 16, 1,
